@@ -1,0 +1,123 @@
+/*
+ * mxfp4.h -- C ABI of libmxfp4: direct conversions between DeepSeek-V3-style blockwise FP8
+ * activations and software MXFP4 on AMD MI355X (gfx950).
+ *
+ * Formats
+ *   FP8 side   : E4M3 bytes (OCP float8_e4m3fn: bias 7, max 448, NaN 0x7F/0xFF, no inf),
+ *                dense row-major [M, K], plus one FP32 scale per 1x128 tile, [M, K/128].
+ *                An element's value is fl32(e4m3 * scale).
+ *   MXFP4 side : E2M1 codes (sign, 2 exponent bits bias 1, 1 mantissa bit; magnitudes
+ *                0 .5 1 1.5 2 3 4 6) packed two per byte -- element 2j in bits 3..0 and
+ *                element 2j+1 in bits 7..4 of byte j -- plus one UE8M0 byte per 32
+ *                elements (byte b = 2^(b-127), b in [0,254]; 0xFF = NaN).
+ *                "Row-blocked": blocks of 1x32 along K, nibbles [M, K/2], scales [M, K/32].
+ *                "Column-blocked": blocks of 32x1 along M, stored transposed: nibbles
+ *                [K, M/2] (even m in the low nibble), scales [K, M/32].
+ *   Payloads   : FP8 = M*K + 4*M*K/128 bytes, MXFP4 = M*K/2 + M*K/32 bytes (paper sec. 3.2).
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees, copies to the host or synchronises; a call enqueues its kernels on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - Outputs must not alias inputs.  Buffers are row-major; K % 128 == 0.
+ *   - Return value: MXFP4_OK, or a negative status; on an error nothing is launched.
+ *     M == 0 (or K == 0) is MXFP4_OK and launches nothing.
+ *   - Only host-visible arguments are validated.  The contents of device arrays
+ *     (gather indices, expert offsets) are trusted; an out-of-range gather index yields a
+ *     zero row rather than an out-of-bounds read.
+ *   - NaN: an E4M3 NaN makes its MXFP4 block's scale byte 0xFF and its 16 packed bytes 0;
+ *     a 0xFF scale byte makes the FP8 tile scale NaN and its block's 32 bytes 0x7F; in the
+ *     row->column conversion it makes every column block it touches 0xFF / 0.
+ *     FP32 tile scales must be finite and >= 0.
+ */
+#ifndef MXFP4_H
+#define MXFP4_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int mxfp4_status;
+
+enum {
+    MXFP4_OK = 0,
+    MXFP4_ERR_NULL = -1,    /* a required pointer is NULL */
+    MXFP4_ERR_SHAPE = -2,   /* negative size, K % 128 != 0, M % 32 != 0 where column blocks are
+                               formed, a row stride smaller than the row, or a size beyond
+                               what the 32-bit work indices of a kernel can address */
+    MXFP4_ERR_ALIGN = -3,   /* pointer or row stride not aligned as stated per entry point */
+    MXFP4_ERR_OFFSETS = -4, /* grouped: num_experts <= 0 or beyond MXFP4_MAX_EXPERTS */
+    MXFP4_ERR_LAUNCH = -5   /* the HIP runtime reported an error at launch */
+};
+
+#define MXFP4_MAX_EXPERTS 1024
+
+/* FP8 -> MXFP4 (paper sec. 3.1: per 1x32 block SF = 2^ceil(log2(max|v| / 6)) as UE8M0, then
+ * round-to-nearest, ties-to-even onto E2M1 with gradual underflow and saturation; applied
+ * directly to the FP8 element values fl32(e4m3 * scale), no BF16 intermediate).
+ *   x          E4M3 [M_src, K], 16-byte aligned
+ *   x_scale    FP32 [M_src, K/128], 4-byte aligned
+ *   gather_idx NULL: M_out must equal M_src and row i <- row i.
+ *              else int32 [M_out] on the device: row i <- row gather_idx[i]
+ *              (quantization placed right before the dispatch: the routing gather is fused).
+ *   q          packed E2M1, M_out rows of K/2 bytes, row stride ld_q bytes (>= K/2);
+ *              pointer and stride 8-byte aligned
+ *   sf         UE8M0, M_out rows of K/32 bytes, row stride ld_sf bytes (>= K/32)
+ * Dense outputs: ld_q = K/2, ld_sf = K/32.  One record per token (nibbles then scales):
+ * ld_q = ld_sf = K/2 + K/32, sf = q + K/2. */
+mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                  const int32_t *gather_idx, int64_t M_out, uint8_t *q,
+                                  int64_t ld_q, uint8_t *sf, int64_t ld_sf, void *hip_stream);
+
+/* MXFP4 -> FP8 (paper sec. 3.3, Algorithm 1: direct bit-wise remap with hierarchical scale
+ * alignment).  Per 128-element tile with scale bytes b0..b3: the FP32 tile scale is
+ * 2^(max(b) - 6 - 127), and every element becomes the E4M3 code of
+ * e2m1(code) * 2^(6 - (max(b) - b_i)) -- the exponent re-bias of Algorithm 1 for normal
+ * codes, rounding to nearest-even through the E4M3 subnormals when the alignment shift
+ * pushes the exponent below 1.  Lossless when max(b) - b_i <= 14.
+ *   q  [M, K/2] with row stride ld_q, 16-byte aligned pointer and stride
+ *   sf [M, K/32] with row stride ld_sf
+ *   x  E4M3 [M, K] dense, 16-byte aligned;  x_scale FP32 [M, K/128] dense, 4-byte aligned */
+mxfp4_status mxfp4_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, int64_t ld_sf,
+                                  int64_t M, int64_t K, uint8_t *x, float *x_scale,
+                                  void *hip_stream);
+
+/* Row-blocked MXFP4 -> column-blocked MXFP4 of the same matrix for the weight-gradient GEMM
+ * (paper sec. 3.4: de-quantization, transposition and re-quantization fused in one pass
+ * through on-chip memory).  Every element takes its exact value e2m1 * 2^(b_row - 127); each
+ * run of 32 consecutive m at fixed k is re-quantized with the rule of sec. 3.1.
+ *   q_row [M, K/2] dense, 4-byte aligned;  sf_row [M, K/32] dense, 4-byte aligned
+ *   q_col [K, M/2] dense, 16-byte aligned; sf_col [K, M/32] dense
+ *   M % 32 == 0. */
+mxfp4_status mxfp4_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                              uint8_t *q_col, uint8_t *sf_col, void *hip_stream);
+
+/* Ragged per-expert forms (paper sec. 3.4, native support for ragged MoE tensors).
+ *   expert_offsets  int32 [num_experts + 1] on the DEVICE: rows [off_e, off_{e+1}) belong to
+ *                   expert e; off_0 = 0, off_E = M_total, non-decreasing, every
+ *                   T_e = off_{e+1} - off_e a multiple of 32 (T_e = 0 allowed).
+ * Quantization is row-independent, so the grouped form produces exactly what the flat form
+ * produces on M_total rows (dense outputs).
+ * Grouped row->column writes expert e as its own dense [K, T_e/2] and [K, T_e/32] matrices
+ * at byte offsets K*off_e/2 and K*off_e/32 of q_col / sf_col: contiguous storage without
+ * padding.  No column block crosses an expert boundary. */
+mxfp4_status mxfp4_quant_from_fp8_grouped(const uint8_t *x, const float *x_scale,
+                                          const int32_t *expert_offsets, int32_t num_experts,
+                                          int64_t M_total, int64_t K, uint8_t *q, uint8_t *sf,
+                                          void *hip_stream);
+
+mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                      const int32_t *expert_offsets, int32_t num_experts,
+                                      int64_t M_total, int64_t K, uint8_t *q_col, uint8_t *sf_col,
+                                      void *hip_stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *mxfp4_status_string(mxfp4_status status);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* MXFP4_H */

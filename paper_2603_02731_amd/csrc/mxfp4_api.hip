@@ -1,0 +1,123 @@
+// The C ABI of libmxfp4 (include/mxfp4.h): argument validation and kernel launches.
+// Nothing here allocates, copies or synchronises.
+#include "../../include/mxfp4.h"
+#include "mxfp4_kernels.hpp"
+
+namespace {
+
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline mxfp4_status launched(hipError_t e) { return e == hipSuccess ? MXFP4_OK : MXFP4_ERR_LAUNCH; }
+
+constexpr int64_t kMaxWorkItems = (int64_t)1 << 32; // kernels index their work with 32 bits
+constexpr int64_t kMaxRows = (int64_t)1 << 31;
+
+} // namespace
+
+extern "C" {
+
+mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                  const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
+                                  uint8_t *sf, int64_t ld_sf, void *hip_stream)
+{
+    if (M_src < 0 || M_out < 0 || K < 0 || K % 128 != 0)
+        return MXFP4_ERR_SHAPE;
+    if (!gather_idx && M_out != M_src)
+        return MXFP4_ERR_SHAPE;
+    if (M_out == 0 || K == 0)
+        return MXFP4_OK;
+    if (!x || !x_scale || !q || !sf)
+        return MXFP4_ERR_NULL;
+    if (gather_idx && M_src == 0)
+        return MXFP4_ERR_SHAPE;
+    if (ld_q < K / 2 || ld_sf < K / 32 || M_src >= kMaxRows || M_out >= kMaxRows || K >= kMaxRows ||
+        M_out * (K / 16) >= kMaxWorkItems)
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(x_scale, 4) || !aligned(q, 8) || ld_q % 8 != 0 ||
+        (gather_idx && !aligned(gather_idx, 4)))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_quant_from_fp8(x, x_scale, M_src, K, gather_idx, M_out, q, ld_q, sf, ld_sf,
+                                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+mxfp4_status mxfp4_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, int64_t ld_sf, int64_t M,
+                                  int64_t K, uint8_t *x, float *x_scale, void *hip_stream)
+{
+    if (M < 0 || K < 0 || K % 128 != 0)
+        return MXFP4_ERR_SHAPE;
+    if (M == 0 || K == 0)
+        return MXFP4_OK;
+    if (!q || !sf || !x || !x_scale)
+        return MXFP4_ERR_NULL;
+    if (ld_q < K / 2 || ld_sf < K / 32 || M >= kMaxRows || K >= kMaxRows || M * (K / 32) >= kMaxWorkItems)
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(q, 16) || ld_q % 16 != 0 || !aligned(x, 16) || !aligned(x_scale, 4))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_dequant_to_fp8(q, ld_q, sf, ld_sf, M, K, x, x_scale,
+                                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+static mxfp4_status row_to_col_common(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                                      int32_t num_experts, int64_t M, int64_t K, uint8_t *q_col,
+                                      uint8_t *sf_col, void *hip_stream)
+{
+    if (M < 0 || K < 0 || K % 128 != 0 || M % 32 != 0)
+        return MXFP4_ERR_SHAPE;
+    if (M == 0 || K == 0)
+        return MXFP4_OK;
+    if (!q_row || !sf_row || !q_col || !sf_col)
+        return MXFP4_ERR_NULL;
+    // grid.y holds one entry per 256-row tile (plus one per expert), grid.y <= 65535;
+    // byte offsets inside a 256-row tile are 32-bit
+    if (M >= kMaxRows || K > ((int64_t)1 << 24) || (M + 255) / 256 + num_experts > 65535)
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(q_row, 4) || !aligned(sf_row, 4) || !aligned(q_col, 16) ||
+        (expert_offsets && !aligned(expert_offsets, 4)))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_row_to_col(q_row, sf_row, expert_offsets, num_experts, M, K, q_col, sf_col,
+                                             static_cast<hipStream_t>(hip_stream)));
+}
+
+mxfp4_status mxfp4_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K, uint8_t *q_col,
+                              uint8_t *sf_col, void *hip_stream)
+{
+    return row_to_col_common(q_row, sf_row, nullptr, 0, M, K, q_col, sf_col, hip_stream);
+}
+
+mxfp4_status mxfp4_quant_from_fp8_grouped(const uint8_t *x, const float *x_scale, const int32_t *expert_offsets,
+                                          int32_t num_experts, int64_t M_total, int64_t K, uint8_t *q,
+                                          uint8_t *sf, void *hip_stream)
+{
+    if (num_experts <= 0 || num_experts > MXFP4_MAX_EXPERTS)
+        return MXFP4_ERR_OFFSETS;
+    if (!expert_offsets)
+        return MXFP4_ERR_NULL;
+    // rows are independent: the expert boundaries do not change any output byte
+    return mxfp4_quant_from_fp8(x, x_scale, M_total, K, nullptr, M_total, q, K / 2, sf, K / 32, hip_stream);
+}
+
+mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                                      int32_t num_experts, int64_t M_total, int64_t K, uint8_t *q_col,
+                                      uint8_t *sf_col, void *hip_stream)
+{
+    if (num_experts <= 0 || num_experts > MXFP4_MAX_EXPERTS)
+        return MXFP4_ERR_OFFSETS;
+    if (!expert_offsets)
+        return MXFP4_ERR_NULL;
+    return row_to_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, q_col, sf_col, hip_stream);
+}
+
+const char *mxfp4_status_string(mxfp4_status status)
+{
+    switch (status) {
+    case MXFP4_OK: return "ok";
+    case MXFP4_ERR_NULL: return "null pointer";
+    case MXFP4_ERR_SHAPE: return "bad shape or stride";
+    case MXFP4_ERR_ALIGN: return "misaligned pointer or stride";
+    case MXFP4_ERR_OFFSETS: return "bad expert count";
+    case MXFP4_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+} // extern "C"

@@ -1,0 +1,82 @@
+// Device-side helpers shared by the gfx950 conversion kernels.
+//
+// Hardware facts the kernels rely on (each checked exhaustively by the GPU parity tests):
+//  * v_cvt_pk_f32_fp8 decodes OCP E4M3 exactly, subnormals and NaN included.
+//  * v_cvt_scalef32_pk_fp4_f32 computes RTNE(src / 2^(E-127)) onto E2M1 with gradual
+//    underflow and saturation, E being bits 30:23 of the scale operand (sign and mantissa
+//    of the scale are ignored, E = 0 means 2^-127), keeps the sign of zero results, and
+//    honours FP32 subnormal sources.
+//  * v_cvt_scalef32_pk_f32_fp4 returns e2m1 * 2^(E-127) exactly, as FP32 subnormals where
+//    needed.
+//  * v_maximum3_f32 propagates NaN.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+#include <utility>
+
+namespace mxfp4 {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+
+// Byte permute: the result's byte i is byte sel[i] of the 8-byte pool {hi:lo}
+// (selector values 0..3 pick from lo, 4..7 from hi).
+__device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel)
+{
+    return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// Value of the lane whose index differs in bit 0 / bit 1 (within a quad), by DPP.
+template <int CTRL>
+__device__ __forceinline__ uint32_t quad_swap(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1; // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E; // quad_perm [2,3,0,1]
+
+// NaN-propagating maximum of |a|, |b| and c.
+__device__ __forceinline__ float max3_abs_nan(float a, float b, float c)
+{
+    return __builtin_elementwise_maximum(
+        __builtin_elementwise_maximum(__builtin_fabsf(a), __builtin_fabsf(b)), c);
+}
+
+// UE8M0 byte of the block scale for a block maximum given as FP32 bits (sign clear):
+// the smallest k with gmax <= 6 * 2^k, biased by 127 and clamped to [0,254]
+// (paper sec. 3.1, evaluated on the exponent field as in sec. 3.4).
+// gmax = 1.f * 2^(e-127): gmax <= 6 * 2^k = 1.5 * 2^(k+2)  <=>  k = e-127-2 when f <= 1.5,
+// one more otherwise.  Zero and FP32 subnormals land on byte 0 through the clamp,
+// +inf gives 254, NaN gives 0xFF.
+__device__ __forceinline__ uint32_t ue8m0_of_block_max(uint32_t gmax_bits)
+{
+    int e = (int)(gmax_bits >> 23);
+    uint32_t mant = gmax_bits & 0x7FFFFFu;
+    int b = e - 2 + (mant > 0x400000u ? 1 : 0);
+    b = b < 0 ? 0 : b;
+    b = gmax_bits == 0x7F800000u ? 254 : b;
+    b = gmax_bits > 0x7F800000u ? 255 : b;
+    return (uint32_t)b;
+}
+
+// Compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>).
+// The conversion builtins take their byte selector as an immediate.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
+}
+
+} // namespace mxfp4

@@ -1,0 +1,22 @@
+// Launchers of the gfx950 kernels (internal to the library; the public boundary is the C
+// ABI in include/mxfp4.h).  Arguments are already validated by the caller.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mxfp4 {
+
+hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                 const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
+                                 uint8_t *sf, int64_t ld_sf, hipStream_t stream);
+
+hipError_t launch_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, int64_t ld_sf,
+                                 int64_t M, int64_t K, uint8_t *x, float *x_scale, hipStream_t stream);
+
+// expert_offsets == nullptr: the flat conversion of an [M, K] matrix.
+hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                             int32_t num_experts, int64_t M, int64_t K, uint8_t *q_col, uint8_t *sf_col,
+                             hipStream_t stream);
+
+} // namespace mxfp4

@@ -1,0 +1,147 @@
+// FP8 (E4M3 + FP32 1x128 scales) -> MXFP4 (packed E2M1 + UE8M0 per 1x32), gfx950.
+//
+// Paper sec. 3.1: SF = 2^ceil(log2(group_max / 6)) per 1x32 block, then RTNE onto E2M1.
+// The element values are the FP8 values themselves, fl32(e4m3 * tile scale): nothing
+// passes through BF16 (the direct FP8 -> FP4 path of the paper's contributions).
+//
+// Work split: one lane owns 16 consecutive elements (one 16-byte load), so a block of 32
+// is a pair of lanes and a 128-tile is 8 lanes.  Per lane:
+//   16 B load -> 8 x v_cvt_pk_f32_fp8 -> 16 x v_mul_f32 (the one FP32 rounding)
+//   -> NaN-propagating |max| (v_maximum3_f32) -> one DPP exchange with the pair lane
+//   -> exponent-field arithmetic for the UE8M0 byte -> 8 x v_cvt_scalef32_pk_fp4_f32
+//   -> one 8-byte store of 16 nibbles; the even lane of a pair stores the scale byte.
+// HBM-bound: 1.03125 B read + 0.53125 B written per element.
+#include "mxfp4_device.hpp"
+#include "mxfp4_kernels.hpp"
+
+namespace mxfp4 {
+
+constexpr int QUANT_THREADS = 256;
+
+struct QuantArgs {
+    const uint8_t *x;
+    const float *x_scale;
+    const int32_t *gather_idx;
+    uint8_t *q;
+    uint8_t *sf;
+    int64_t ld_q;
+    int64_t ld_sf;
+    uint32_t n_chunks;       // M_out * K / 16
+    uint32_t chunks_per_row; // K / 16
+    uint32_t K;
+    uint32_t M_src;
+};
+
+// Quantize the lane's 16 elements given as four dwords of E4M3 bytes and the tile scale.
+// Returns the 16 nibbles in out[0..1]; *scale_byte is the block's UE8M0 byte (identical
+// in both lanes of the pair).
+__device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2], uint32_t *scale_byte)
+{
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[j], false);
+        f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[j], true);
+        v[4 * j + 0] = lo.x * s;
+        v[4 * j + 1] = lo.y * s;
+        v[4 * j + 2] = hi.x * s;
+        v[4 * j + 3] = hi.y * s;
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; j += 2)
+        m = max3_abs_nan(v[j], v[j + 1], m);
+    float other = u2f(quad_swap<DPP_QUAD_XOR1>(f2u(m)));
+    m = __builtin_elementwise_maximum(m, other);
+
+    uint32_t b = ue8m0_of_block_max(f2u(m));
+    float sc = u2f(b << 23); // only the exponent field of the scale operand is used
+    uint32_t r0 = 0, r1 = 0;
+    r0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r0, v[0], v[1], sc, 0);
+    r0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r0, v[2], v[3], sc, 1);
+    r0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r0, v[4], v[5], sc, 2);
+    r0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r0, v[6], v[7], sc, 3);
+    r1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r1, v[8], v[9], sc, 0);
+    r1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r1, v[10], v[11], sc, 1);
+    r1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r1, v[12], v[13], sc, 2);
+    r1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r1, v[14], v[15], sc, 3);
+    const bool nan_block = b == 255u; // a NaN poisons the block: codes are zeroed
+    out[0] = nan_block ? 0u : r0;
+    out[1] = nan_block ? 0u : r1;
+    *scale_byte = b;
+}
+
+// DENSE: no gather and dense outputs -- every address is a multiple of the flat chunk index.
+template <bool DENSE>
+__global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const QuantArgs a)
+{
+    const uint32_t c = blockIdx.x * QUANT_THREADS + threadIdx.x;
+    if (c >= a.n_chunks)
+        return; // n_chunks is a multiple of 8, so the two lanes of a pair exit together
+
+    const uint8_t *src;
+    const float *src_scale;
+    uint8_t *dst_q;
+    uint8_t *dst_sf;
+    bool valid = true;
+    if (DENSE) {
+        src = a.x + (size_t)c * 16;
+        src_scale = a.x_scale + (c >> 3);
+        dst_q = a.q + (size_t)c * 8;
+        dst_sf = a.sf + (c >> 1);
+    } else {
+        const uint32_t row = c / a.chunks_per_row;
+        const uint32_t cc = c - row * a.chunks_per_row;
+        uint32_t src_row = row;
+        if (a.gather_idx) {
+            src_row = (uint32_t)a.gather_idx[row];
+            valid = src_row < a.M_src; // also rejects negative indices
+            src_row = valid ? src_row : 0u;
+        }
+        src = a.x + (size_t)src_row * a.K + (size_t)cc * 16;
+        src_scale = a.x_scale + (size_t)src_row * (a.K >> 7) + (cc >> 3);
+        dst_q = a.q + (size_t)row * a.ld_q + (size_t)cc * 8;
+        dst_sf = a.sf + (size_t)row * a.ld_sf + (cc >> 1);
+    }
+
+    u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+    float s = *src_scale;
+    if (!valid) {
+        w = u32x4{0u, 0u, 0u, 0u};
+        s = 0.0f;
+    }
+
+    uint32_t out[2], b;
+    quant16(w, s, out, &b);
+
+    __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q));
+    if ((threadIdx.x & 1u) == 0u)
+        *dst_sf = (uint8_t)b;
+}
+
+hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                 const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
+                                 uint8_t *sf, int64_t ld_sf, hipStream_t stream)
+{
+    QuantArgs a;
+    a.x = x;
+    a.x_scale = x_scale;
+    a.gather_idx = gather_idx;
+    a.q = q;
+    a.sf = sf;
+    a.ld_q = ld_q;
+    a.ld_sf = ld_sf;
+    a.n_chunks = (uint32_t)(M_out * (K / 16));
+    a.chunks_per_row = (uint32_t)(K / 16);
+    a.K = (uint32_t)K;
+    a.M_src = (uint32_t)M_src;
+    const uint32_t blocks = (a.n_chunks + QUANT_THREADS - 1) / QUANT_THREADS;
+    const bool dense = gather_idx == nullptr && ld_q == K / 2 && ld_sf == K / 32;
+    if (dense)
+        hipLaunchKernelGGL(quant_from_fp8_kernel<true>, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+    else
+        hipLaunchKernelGGL(quant_from_fp8_kernel<false>, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace mxfp4

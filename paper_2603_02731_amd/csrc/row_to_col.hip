@@ -1,0 +1,313 @@
+// Row-blocked MXFP4 -> column-blocked MXFP4 (stored transposed), gfx950.
+//
+// Paper sec. 3.4: de-quantization, transposition and re-quantization fused into one pass
+// through on-chip memory, so the matrix is read once and written once.  Every element
+// takes its exact value e2m1 * 2^(b_row - 127); each 32x1 run along m is re-quantized with
+// the scale rule and rounding of sec. 3.1.
+//
+// Work split.  A workgroup of 256 lanes owns a 256 (m) x 256 (k) tile, the unit that makes
+// both global reads and global writes 128-byte contiguous.  Inside, the unit of work is the
+// 32x32 block of the method: lane (rg, cg) owns rows 32*rg..32*rg+31 and the 8 columns
+// 8*cg..8*cg+7, i.e. one 32x8 slice of a 32x32 block, as 32 dwords of nibbles (one per row).
+//   pass 1: v_cvt_scalef32_pk_f32_fp4 (row scale applied by the instruction, two columns
+//           per issue) and a running |max| per column -> 8 column maxima -> 8 UE8M0 bytes
+//           by exponent-field arithmetic.
+//   pass 2: the same decode again (cheaper than keeping 256 floats live), then
+//           v_cvt_scalef32_pk_fp4_f32 takes the values of rows (m, m+1) of one column and
+//           emits the output byte directly: the register pairing IS the transposition of
+//           the 32x32 block, no nibble shuffling is needed.
+// The 8 x 16 B per lane then go through an LDS tile (swizzled so that both the 16-byte
+// writes and the linear read-back are bank-conflict free) to leave as full 128-byte rows.
+// HBM-bound: 0.53125 B read + 0.53125 B written per element.
+#include "mxfp4_device.hpp"
+#include "mxfp4_kernels.hpp"
+
+namespace mxfp4 {
+
+constexpr int T_THREADS = 256;
+constexpr int TILE_M = 256;
+constexpr int TILE_K = 256;
+
+struct RowToColArgs {
+    const uint8_t *q_row;
+    const uint8_t *sf_row;
+    uint8_t *q_col;
+    uint8_t *sf_col;
+    const int32_t *expert_offsets; // nullptr: one group of M rows
+    int32_t num_experts;
+    uint32_t M; // total rows
+    uint32_t K;
+};
+
+// Byte i%4 of dword i/4.
+template <int I>
+__device__ __forceinline__ uint32_t row_byte(const uint32_t (&sb)[8])
+{
+    return (sb[I >> 2] >> (8 * (I & 3))) & 0xFFu;
+}
+
+// One lane's 32x8 slice through the hardware conversions.  Exact while every value
+// e2m1 * 2^(b-127) is an FP32 number, i.e. for row-scale bytes up to 252
+// (6 * 2^125 < 2^128; the smallest, 0.5 * 2^-127, is an FP32 subnormal).
+__device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&sb)[8], uint32_t (&cb)[8],
+                                                 uint32_t (&o)[8][4])
+{
+    // pass 1: column maxima of |value|.  The scale operand of a row is its byte moved into
+    // the FP32 exponent field; it is rebuilt where it is used rather than kept in 32 registers.
+    float amax[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        amax[c] = 0.0f;
+    static_for<16>([&](auto ip) {
+        constexpr int i = 2 * decltype(ip)::value;
+        const float sa = u2f(row_byte<i>(sb) << 23), sbb = u2f(row_byte<i + 1>(sb) << 23);
+        static_for<4>([&](auto jp) {
+            constexpr int j = decltype(jp)::value;
+            const f32x2 fa = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sa, j);
+            const f32x2 fb = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i + 1], sbb, j);
+            amax[2 * j] = max3_abs_nan(fa.x, fb.x, amax[2 * j]);
+            amax[2 * j + 1] = max3_abs_nan(fa.y, fb.y, amax[2 * j + 1]);
+        });
+    });
+
+    // column scales (sec. 3.1 rule on the exponent field)
+    float cs[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        cb[c] = ue8m0_of_block_max(f2u(amax[c]));
+        cs[c] = u2f(cb[c] << 23);
+    }
+
+    // pass 2: decode again (cheaper than 256 live floats), re-quantize pairs of rows into
+    // output bytes.
+    // The empty asm statements make the nibble and scale registers opaque and dependent on
+    // all eight column scales: every decode of pass 2 is a new computation that cannot start
+    // before pass 1 has finished, so the 256 floats of pass 1 are never kept alive.
+#define MXFP4_TIE8(x0, x1, x2, x3, x4, x5, x6, x7)                                                          \
+    asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7)       \
+                 : "v"(cs[0]), "v"(cs[1]), "v"(cs[2]), "v"(cs[3]), "v"(cs[4]), "v"(cs[5]), "v"(cs[6]), "v"(cs[7]))
+    MXFP4_TIE8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
+    MXFP4_TIE8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
+    MXFP4_TIE8(w[16], w[17], w[18], w[19], w[20], w[21], w[22], w[23]);
+    MXFP4_TIE8(w[24], w[25], w[26], w[27], w[28], w[29], w[30], w[31]);
+    MXFP4_TIE8(sb[0], sb[1], sb[2], sb[3], sb[4], sb[5], sb[6], sb[7]);
+#undef MXFP4_TIE8
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            o[c][g] = 0u;
+    static_for<16>([&](auto ip) {
+        constexpr int i = 2 * decltype(ip)::value;
+        constexpr int g = i >> 3, sel = (i >> 1) & 3; // output dword and byte of rows (i, i+1)
+        const float sa = u2f(row_byte<i>(sb) << 23), sbb = u2f(row_byte<i + 1>(sb) << 23);
+        static_for<4>([&](auto jp) {
+            constexpr int j = decltype(jp)::value;
+            const f32x2 fa = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sa, j);
+            const f32x2 fb = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i + 1], sbb, j);
+            o[2 * j][g] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o[2 * j][g], fa.x, fb.x, cs[2 * j], sel);
+            o[2 * j + 1][g] =
+                __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o[2 * j + 1][g], fa.y, fb.y, cs[2 * j + 1], sel);
+        });
+    });
+}
+
+// The same slice in integers, for row-scale bytes 253 and 254, whose largest values
+// (4 and 6 times 2^126 or 2^127) exceed FP32.  Never taken by real activations, so it is
+// written for size, not speed: rolled loops that re-read the nibbles (they are still in
+// cache) and the staged row scales, and write straight into the LDS output tile.
+// Every non-zero E2M1 value is (1 + M/2) * 2^(E-1) with the pair (E, M) = (field, mantissa),
+// except the subnormal 0.5 = 1.0 * 2^-1, i.e. (0, 0).  With at most two significant bits,
+// ceil(log2(x/6)) = floor(log2 x) - 2, so the column byte is max(0, max(b_row + E) - 3).
+// Relative to it, t = 2*(b_row + E - b_col) + M orders the values; t >= 2 are E2M1 normals
+// and stay exact (code t), and below that RTNE gives t = 1 -> 1.0 (tie .75, even code 2),
+// t = 0 and -1 -> 0.5 (code 1), t = -2 -> 0 (tie .25), lower -> 0.
+__device__ __noinline__ void requant_slice_int(const uint8_t *src, size_t src_pitch, const uint8_t *row_sf,
+                                               uint32_t *out_row0, uint32_t out_row_stride, uint8_t *col_sf0,
+                                               uint32_t col_sf_stride)
+{
+#pragma nounroll
+    for (int c = 0; c < 8; ++c) {
+        int emax = -1024;
+#pragma nounroll
+        for (int i = 0; i < 32; ++i) {
+            const uint32_t wi = *reinterpret_cast<const uint32_t *>(src + (size_t)i * src_pitch);
+            const int mag = (int)(wi >> (4 * c)) & 7;
+            if (mag)
+                emax = max(emax, (int)row_sf[i] + (mag >> 1));
+        }
+        const int bc = max(0, emax - 3);
+        col_sf0[c * col_sf_stride] = (uint8_t)bc;
+#pragma nounroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t acc = 0;
+#pragma nounroll
+            for (int i8 = 0; i8 < 8; ++i8) {
+                const int i = g * 8 + i8;
+                const uint32_t wi = *reinterpret_cast<const uint32_t *>(src + (size_t)i * src_pitch);
+                const uint32_t nib = (wi >> (4 * c)) & 0xFu;
+                const int mag = (int)(nib & 7u);
+                const int em = mag == 1 ? 0 : mag; // 2*E + M of the normalised value
+                const int t2 = max(em + 2 * ((int)row_sf[i] - bc) + 2, 0);
+                int code = min(7, max(t2 - 2, (t2 + 1) >> 1));
+                code = mag ? code : 0;
+                acc |= ((nib & 8u) | (uint32_t)code) << (4 * i8);
+            }
+            out_row0[c * out_row_stride + g] = acc;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArgs a)
+{
+    __shared__ u32x4 s_out[TILE_K * 8];                   // [c*32 + cg][slot]: 256 k-rows x 128 B
+    __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
+    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * 8]; // [k][row group]
+
+    // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
+    uint32_t row_base = 0, rows = a.M, tile = blockIdx.y;
+    if (a.expert_offsets) {
+        bool found = false;
+        for (int e = 0; e < a.num_experts; ++e) {
+            const uint32_t lo = (uint32_t)a.expert_offsets[e], hi = (uint32_t)a.expert_offsets[e + 1];
+            const uint32_t nt = (hi - lo + TILE_M - 1) / TILE_M;
+            if (tile < nt) {
+                row_base = lo;
+                rows = hi - lo;
+                found = true;
+                break;
+            }
+            tile -= nt;
+        }
+        if (!found)
+            return;
+    }
+    const uint32_t m0 = tile * TILE_M;
+    if (m0 >= rows)
+        return;
+    const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
+    const uint32_t k0 = blockIdx.x * TILE_K;
+    const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
+    const uint32_t Kb = a.K / 32u;
+
+    // expert e's output is its own dense [K, rows/2] and [K, rows/32]
+    uint8_t *out_q = a.q_col + (size_t)a.K * row_base / 2;
+    uint8_t *out_sf = a.sf_col + (size_t)a.K * row_base / 32;
+    const size_t pitch_q = rows / 2, pitch_sf = rows / 32;
+
+    const uint32_t tid = threadIdx.x;
+
+    // ---- stage the tile's row scales: thread t takes row t, 4 or 8 bytes
+    if (tid < n_rg * 32u) {
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(
+            a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u);
+        const uint32_t lo = p[0];
+        const uint32_t hi = cols > 128u ? p[1] : 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
+            s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
+        }
+    }
+    __syncthreads();
+
+    const uint32_t rg = tid >> 5, cg = tid & 31u;
+    const bool active = rg < n_rg && cg * 8u < cols;
+
+    if (active) {
+        // ---- load the 32x8 slice: one dword (8 nibbles) per row
+        // (a uniform row pointer plus a 32-bit lane offset: one address register, not 32 pairs)
+        uint32_t w[32];
+        const uint32_t pitch = a.K / 2u;
+        const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
+        const uint32_t lane_off = rg * 32u * pitch + cg * 4u; // < 2^32: K is at most 2^24
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            w[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+
+        // the 32 row-scale bytes of this slice: 8 dwords, byte i%4 of dword i/4 is row i
+        uint32_t sb[8];
+        {
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(&s_row_sf[(cg >> 2) * TILE_M + rg * 32u]);
+            const u32x4 s0 = p[0], s1 = p[1];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                sb[g] = s0[g];
+                sb[4 + g] = s1[g];
+            }
+        }
+        uint32_t sf_max = 0;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            sf_max = max(sf_max, (sb[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+        const bool poisoned = sf_max == 255u; // a NaN row scale touches all 8 columns
+
+        // ---- results go to LDS: row (c*32 + cg), 16-byte slot rotated by cg/2, so that 16
+        // consecutive lanes cover 256 consecutive-bank bytes and the read-back below is linear
+        const uint32_t slot = (rg + (cg >> 1)) & 7u;
+        if (sf_max < 253u || poisoned) {
+            uint32_t cb[8];   // column scale bytes
+            uint32_t o[8][4]; // per column: 32 output nibbles (rows 0..31 of the slice)
+            requant_slice_hw(w, sb, cb, o);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                u32x4 v = poisoned ? u32x4{0u, 0u, 0u, 0u} : u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
+                s_out[(c * 32 + cg) * 8 + slot] = v;
+                s_col_sf[(cg * 8 + c) * 8 + rg] = (uint8_t)(poisoned ? 255u : cb[c]);
+            }
+        } else {
+            requant_slice_int(tile_src + lane_off, pitch, &s_row_sf[(cg >> 2) * TILE_M + rg * 32u],
+                              reinterpret_cast<uint32_t *>(&s_out[cg * 8 + slot]), 32 * 8 * 4,
+                              &s_col_sf[cg * 8 * 8 + rg], 8);
+        }
+    }
+    __syncthreads();
+
+    // ---- write the tile out: 8 lanes per k-row, 128 contiguous bytes each
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const uint32_t f = u * T_THREADS + tid;
+        const uint32_t r = f >> 3, slot = f & 7u;
+        const uint32_t cgx = r & 31u, c = r >> 5;
+        const uint32_t k = cgx * 8u + c;
+        const uint32_t part = (slot - (cgx >> 1)) & 7u; // row group held in this slot
+        if (k < cols && part < n_rg) {
+            u32x4 *dst = reinterpret_cast<u32x4 *>(out_q + (size_t)(k0 + k) * pitch_q + m0 / 2u + part * 16u);
+            *dst = s_out[f];
+        }
+    }
+    if (tid < cols) {
+        uint8_t *dst = out_sf + (size_t)(k0 + tid) * pitch_sf + m0 / 32u;
+        const uint32_t *sp = reinterpret_cast<const uint32_t *>(&s_col_sf[tid * 8]);
+        if (n_rg == 8u && (reinterpret_cast<uintptr_t>(dst) & 3u) == 0u) {
+            reinterpret_cast<uint32_t *>(dst)[0] = sp[0];
+            reinterpret_cast<uint32_t *>(dst)[1] = sp[1];
+        } else {
+            for (uint32_t g = 0; g < n_rg; ++g)
+                dst[g] = s_col_sf[tid * 8 + g];
+        }
+    }
+}
+
+hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                             int32_t num_experts, int64_t M, int64_t K, uint8_t *q_col, uint8_t *sf_col,
+                             hipStream_t stream)
+{
+    RowToColArgs a;
+    a.q_row = q_row;
+    a.sf_row = sf_row;
+    a.q_col = q_col;
+    a.sf_col = sf_col;
+    a.expert_offsets = expert_offsets;
+    a.num_experts = num_experts;
+    a.M = (uint32_t)M;
+    a.K = (uint32_t)K;
+    // upper bound on the number of 256-row tiles: every expert may end in a partial tile
+    const int64_t m_tiles = (M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0);
+    const dim3 grid((uint32_t)((K + TILE_K - 1) / TILE_K), (uint32_t)m_tiles);
+    hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace mxfp4

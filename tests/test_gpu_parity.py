@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+
+Every comparison is exact equality of packed nibbles, scale bytes, E4M3 bytes and FP32
+scale bit patterns.  Sizes span several tiles and ragged tails; the edge cases of each
+conversion (zero blocks, NaN, subnormals, saturation, huge scale spreads) are included.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_02731_amd as mx
+from oracle import ref
+from paper_2603_02731_amd import synth
+from tests import par
+from tests.test_oracle_quant import scale_sweep
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.as_tensor(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_same(got, want, what):
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if got.dtype == np.float32:
+        got, want = got.view(np.uint32), want.view(np.uint32)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{what}: {len(bad)} mismatches, first at {bad[0].tolist()}: " \
+                          f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}"
+
+
+def check_quant(x8, s, **kw):
+    q, sf = mx.mxfp4_quant_from_fp8(dev(x8), dev(s), **kw)
+    wq, wsf = par.quant(x8, s)
+    assert_same(host(sf), wsf, "quant scale bytes")
+    assert_same(host(q), wq, "quant nibbles")
+    return wq, wsf
+
+
+def check_dequant(q, sf):
+    x, xs = mx.mxfp4_dequant_to_fp8(dev(q), dev(sf))
+    wx, wxs = par.dequant(q, sf)
+    assert_same(host(xs), wxs, "dequant tile scales")
+    assert_same(host(x), wx, "dequant E4M3 bytes")
+
+
+def check_row_to_col(q, sf):
+    qc, sc = mx.mxfp4_row_to_col(dev(q), dev(sf))
+    wq, ws = par.row_to_col(q, sf)
+    assert_same(host(sc), ws, "row->col scale bytes")
+    assert_same(host(qc), wq, "row->col nibbles")
+
+
+# ------------------------------------------------------------------ config 1: tiny round trip
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config1_round_trip_and_row_to_col(seed):
+    x8, s = synth.tiny_roundtrip_fp8(seed=seed)
+    x8, s = x8.numpy(), s.numpy()
+    q, sf = check_quant(x8, s)
+    check_dequant(q, sf)
+    check_row_to_col(q, sf)
+
+
+# ------------------------------------------------------------------ quant: exhaustive codes x scales
+
+def test_quant_all_codes_times_scale_sweep():
+    rng = np.random.default_rng(0)
+    scales = scale_sweep()
+    scales += [float(np.float32(rng.uniform(1e-3, 10.0)) / np.float32(448)) for _ in range(200)]
+    scales += [float(np.float32(2.0 ** rng.uniform(-149, 118))) for _ in range(200)]
+    rows_x, rows_s = [], []
+    for s in scales:
+        # every code once, shuffled over 8 blocks; then every code under small block maxima
+        perm = rng.permutation(256).astype(np.uint8)
+        rows_x.append(perm.reshape(2, 128))
+        rows_s.append(np.full((2, 1), s, np.float32))
+        small = (rng.integers(0, 256, size=(2, 128)) & 0x8F | rng.integers(0, 0x30, size=(2, 128))).astype(np.uint8)
+        rows_x.append(small)
+        rows_s.append(np.full((2, 1), s, np.float32))
+    x8 = np.concatenate(rows_x)
+    s = np.concatenate(rows_s)
+    pad = (-x8.shape[0]) % 7                      # K = 128*7 so that rows hold several tiles
+    x8 = np.concatenate([x8, np.zeros((pad, 128), np.uint8)]).reshape(-1, 128 * 7)
+    s = np.concatenate([s, np.ones((pad, 1), np.float32)]).reshape(-1, 7)
+    check_quant(x8, s)
+
+
+def test_quant_every_code_under_every_block_maximum():
+    rows = []
+    for cmax in range(1, 0x7F):
+        others = np.arange(0, cmax + 1)
+        for i in range(0, len(others), 31):
+            blk = np.concatenate([[cmax], others[i:i + 31]])
+            blk = np.concatenate([blk, np.zeros(32 - len(blk), np.int64)])
+            sign = ((np.arange(32) + cmax) % 3 == 0) * 0x80
+            rows.append((blk | sign).astype(np.uint8))
+    rows += [np.zeros(32, np.uint8)] * ((-len(rows)) % 4)
+    x8 = np.stack(rows).reshape(-1, 128)
+    for sval in [1.0, 2.0 ** -131, 2.0 ** 118, 0.0123, 3.3e-38, 1.7e36]:
+        check_quant(x8, np.full((x8.shape[0], 1), sval, np.float32))
+
+
+def test_quant_nan_inf_zero_blocks():
+    x8, s = synth.student_t_fp8(96, 1024, seed=3)
+    x8, s = x8.numpy().copy(), s.numpy().copy()
+    x8[3, 5] = 0x7F
+    x8[3, 700] = 0xFF
+    x8[10, 32:64] = 0
+    x8[11, :] = 0x80
+    s[20, 2] = 0.0
+    s[21, 1] = np.finfo(np.float32).max / 8      # products overflow to inf
+    s[22, 0] = 2.0 ** -149
+    s[23, 3] = 2.0 ** -140
+    check_quant(x8, s)
+
+
+# ------------------------------------------------------------------ dequant
+
+@pytest.mark.parametrize("center,spread,nan", [(127, 0, 0.0), (127, 3, 0.0), (120, 9, 0.01), (60, 25, 0.0),
+                                              (8, 8, 0.0), (250, 4, 0.02), (127, 127, 0.0)])
+def test_dequant_random_codes_and_scale_spreads(center, spread, nan):
+    q, sf = synth.random_mxfp4(96, 1152, seed=center + spread, scale_center=center, scale_spread=spread,
+                               nan_scale_frac=nan)
+    check_dequant(q.numpy(), sf.numpy())
+
+
+def test_dequant_every_shift_and_code():
+    # block 1 of each tile sits d binades under the tile maximum, d = 0..40; all 16 codes
+    rows_q, rows_s = [], []
+    for bmax in (254, 140, 41, 20, 6, 3):
+        for d in range(0, 41):
+            if bmax - d < 0:
+                continue
+            nib = np.tile(np.arange(16, dtype=np.uint8), 8)
+            rows_q.append((nib[0::2] | (nib[1::2] << 4)).astype(np.uint8))
+            rows_s.append(np.array([bmax, bmax - d, max(bmax - d // 2, 0), bmax - d], np.uint8))
+    pad = (-len(rows_q)) % 3
+    rows_q += [np.zeros(64, np.uint8)] * pad
+    rows_s += [np.zeros(4, np.uint8)] * pad
+    check_dequant(np.stack(rows_q).reshape(-1, 192), np.stack(rows_s).reshape(-1, 12))
+
+
+# ------------------------------------------------------------------ row -> col
+
+@pytest.mark.parametrize("M,K,center,spread,nan", [
+    (256, 256, 127, 0, 0.0), (288, 384, 127, 3, 0.0), (32, 128, 100, 8, 0.0), (544, 640, 30, 30, 0.0),
+    (96, 1152, 4, 6, 0.0), (320, 256, 250, 5, 0.0), (512, 512, 127, 127, 0.0), (352, 384, 120, 4, 0.003)])
+def test_row_to_col_random_codes_and_scale_spreads(M, K, center, spread, nan):
+    q, sf = synth.random_mxfp4(M, K, seed=M + K + spread, scale_center=center, scale_spread=spread,
+                               nan_scale_frac=nan)
+    q, sf = q.numpy().copy(), sf.numpy()
+    q[:, 5] = 0                                   # two all-zero columns
+    q[7::32, :] &= 0x88                           # rows of signed zeros
+    check_row_to_col(q, sf)
+
+
+def test_row_to_col_on_quantized_swiglu():
+    x8, s = synth.swiglu_fp8(1024, 2048, seed=1)
+    q, sf = par.quant(x8.numpy(), s.numpy())
+    check_row_to_col(q, sf)
+
+
+# ------------------------------------------------------------------ grouped, gather, records
+
+def test_grouped_variants_small():
+    off, counts = synth.expert_offsets(seed=1, num_experts=7, total_tokens=1500, pad_to=32)
+    M = int(off[-1])
+    x8, s = synth.student_t_fp8(M, 512, seed=2)
+    x8, s = synth.zero_padding_rows(x8, s, off, counts)
+    x8, s = x8.numpy(), s.numpy()
+    q, sf = mx.mxfp4_quant_from_fp8_grouped(dev(x8), dev(s), off.to(DEV))
+    wq, wsf = ref.quant_from_fp8_grouped(x8, s, off.numpy())
+    assert_same(host(q), wq, "grouped quant nibbles")
+    assert_same(host(sf), wsf, "grouped quant scales")
+    qc, sc = mx.mxfp4_row_to_col_grouped(dev(wq), dev(wsf), off.to(DEV))
+    wqc, wsc = ref.row_to_col_grouped(wq, wsf, off.numpy())
+    assert_same(host(sc), wsc, "grouped row->col scales")
+    assert_same(host(qc), wqc, "grouped row->col nibbles")
+
+
+def test_grouped_with_empty_experts():
+    off = torch.tensor([0, 0, 320, 320, 352, 864, 864], dtype=torch.int32)
+    q, sf = synth.random_mxfp4(864, 384, seed=5, scale_center=125, scale_spread=4)
+    q, sf = q.numpy(), sf.numpy()
+    qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), off.to(DEV))
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off.numpy())
+    assert_same(host(sc), wsc, "grouped row->col scales")
+    assert_same(host(qc), wqc, "grouped row->col nibbles")
+
+
+def test_gather_and_token_records():
+    x8, s = synth.student_t_fp8(300, 1024, seed=6)
+    idx = synth.routing_indices(seed=7, num_tokens=300, top_k=8)
+    x8, s = x8.numpy(), s.numpy()
+    wq, wsf = ref.quant_from_fp8(x8, s, gather_idx=idx.numpy())
+    q, sf = mx.mxfp4_quant_from_fp8(dev(x8), dev(s), gather_idx=idx.to(DEV))
+    assert_same(host(q), wq, "gathered nibbles")
+    assert_same(host(sf), wsf, "gathered scales")
+    # one record per token: K/2 nibble bytes then K/32 scale bytes
+    K = 1024
+    rec = K // 2 + K // 32
+    buf = torch.zeros(idx.shape[0] * rec, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8(dev(x8), dev(s), gather_idx=idx.to(DEV), q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec)
+    recs = host(buf).reshape(-1, rec)
+    assert_same(recs[:, :K // 2], wq, "record nibbles")
+    assert_same(recs[:, K // 2:], wsf, "record scales")
+    # and back: dequantize straight from the records
+    x, xs = mx.mxfp4_dequant_to_fp8(buf, buf[K // 2:], M=idx.shape[0], K=K, ld_q=rec, ld_sf=rec)
+    wx, wxs = par.dequant(wq, wsf)
+    assert_same(host(x), wx, "dequant from records")
+    assert_same(host(xs), wxs, "dequant scales from records")
+    # an out-of-range index yields a zero row, not a fault
+    bad = idx.clone()
+    bad[3], bad[11] = -1, 300
+    q, sf = mx.mxfp4_quant_from_fp8(dev(x8), dev(s), gather_idx=bad.to(DEV))
+    q, sf = host(q), host(sf)
+    assert not q[3].any() and not sf[3].any() and not q[11].any() and not sf[11].any()
+    keep = np.ones(len(bad), bool)
+    keep[[3, 11]] = False
+    assert_same(q[keep], wq[keep], "rows next to a bad index")
+
+
+def test_empty_and_argument_errors():
+    z8 = torch.empty((0, 256), dtype=torch.uint8, device=DEV)
+    zs = torch.empty((0, 2), dtype=torch.float32, device=DEV)
+    q, sf = mx.mxfp4_quant_from_fp8(z8, zs)
+    assert q.shape == (0, 128) and sf.shape == (0, 8)
+    x8 = torch.zeros((32, 256), dtype=torch.uint8, device=DEV)
+    xs = torch.ones((32, 2), dtype=torch.float32, device=DEV)
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_quant_from_fp8(x8[:, :192].contiguous(), xs)          # K % 128 != 0
+    assert e.value.status == -2
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_quant_from_fp8(x8.reshape(-1)[1:257].reshape(1, 256), xs[:1])   # misaligned
+    assert e.value.status == -3
+    q, sf = mx.mxfp4_quant_from_fp8(x8, xs)
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_row_to_col(q[:16], sf[:16])                            # M % 32 != 0
+    assert e.value.status == -2
