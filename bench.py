@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the FP8 <-> MXFP4 conversion hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic DeepSeek-V3-shaped
+activations [65536, 7168]:  FP8 -> MXFP4 quantization, MXFP4 -> FP8 de-quantization, and
+row-blocked -> column-blocked MXFP4 conversion.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line: whole-step algorithmic GB/s as `value`, the roofline of the
+dominant kernel (HIP-event durations taken inside the timed region), per-kernel figures,
+and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+# algorithmic bytes per element (paper sec. 3.2: FP8 = 1 + 4/128, MXFP4 = 1/2 + 1/32)
+BYTES_PER_ELEM = {"quant": 1.03125 + 0.53125, "dequant": 0.53125 + 1.03125, "row_to_col": 0.53125 + 0.53125}
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--rows", type=int, default=65536, help="M of the workload (tokens)")
+    p.add_argument("--hidden", type=int, default=7168, help="K of the workload")
+    p.add_argument("--seed", type=int, default=0)
+    p.add_argument("--cpu-sample-rows", type=int, default=32768)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--variants", action="store_true",
+                   help="also time the gathered, record-layout and grouped entry points (extra JSON field)")
+    return p.parse_args()
+
+
+def cpu_baseline(x8, s, rows):
+    """The oracle as it stands, over `rows` rows of the same workload, one thread per host core."""
+    import numpy as np
+    from oracle import parallel as par  # thread pool over row ranges around the oracle
+    workers = par.WORKERS
+    xs, ss = x8[:rows].cpu().numpy(), s[:rows].cpu().numpy()
+    t0 = time.perf_counter()
+    q, sf = par.quant(xs, ss, workers)
+    t1 = time.perf_counter()
+    par.dequant(q, sf, workers)
+    t2 = time.perf_counter()
+    par.row_to_col(q, sf, workers)
+    t3 = time.perf_counter()
+    n = xs.size
+    total_bytes = n * sum(BYTES_PER_ELEM.values())
+    return {
+        "value": total_bytes / (t3 - t0) * 1e-9, "unit": "GB/s", "cores": workers, "kind": "oracle",
+        "sample": f"first {rows} rows x {xs.shape[1]} of the workload, quant+dequant+row_to_col, "
+                  f"row ranges over {workers} threads",
+        "elements_per_s": {"quant": n / (t1 - t0), "dequant": n / (t2 - t1), "row_to_col": n / (t3 - t2)},
+        "seconds": t3 - t0,
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU; there is no multi-GPU path "
+                         "(the conversions shard by rows with no exchange). Use --gpus 1.\n")
+        sys.exit(2)
+
+    import torch
+    import paper_2603_02731_amd as mx
+    from paper_2603_02731_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    mx.lib()  # fail loudly here if the HIP library is missing
+
+    M, K = a.rows, a.hidden
+    x8, s = synth.student_t_fp8(M, K, seed=a.seed, device=dev)
+    q = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+    sf = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
+    xb = torch.empty((M, K), dtype=torch.uint8, device=dev)
+    sb = torch.empty((M, K // 128), dtype=torch.float32, device=dev)
+    qc = torch.empty((K, M // 2), dtype=torch.uint8, device=dev)
+    sc = torch.empty((K, M // 32), dtype=torch.uint8, device=dev)
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        mx.mxfp4_quant_from_fp8(x8, s, q=q, sf=sf)
+        if ev:
+            ev[1].record()
+        mx.mxfp4_dequant_to_fp8(q, sf, x=xb, x_scale=sb)
+        if ev:
+            ev[2].record()
+        mx.mxfp4_row_to_col(q, sf, q_col=qc, sf_col=sc)
+        if ev:
+            ev[3].record()
+
+    for _ in range(a.warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / a.steps
+
+    n = M * K
+    names = ["quant", "dequant", "row_to_col"]
+    kernels = {}
+    for j, name in enumerate(names):
+        us = sum(e[j].elapsed_time(e[j + 1]) for e in events) * 1e3 / a.steps
+        b = n * BYTES_PER_ELEM[name]
+        kernels[name] = {"us": us, "GB/s": b / us * 1e-3, "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS,
+                         "elements_per_s": n / us * 1e6, "algorithmic_bytes": b}
+    total_bytes = n * sum(BYTES_PER_ELEM.values())
+    value = total_bytes / (ms_per_step * 1e-3) * 1e-9
+    dom = max(names, key=lambda k: kernels[k]["us"])
+
+    out = {
+        "metric": "HBM GB/s (% of peak) for FP8<->MXFP4 quant/dequant and MXFP4 row->col",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"target_{M}x{K}: Student-t(df=3) activations with 1% outlier channels x100, "
+                               f"FP8 E4M3 + FP32 1x128 scales; step = quant + dequant + row_to_col",
+                   "rows": M, "hidden": K, "seed": a.seed},
+        "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
+        "elements_per_s": 3 * n / (ms_per_step * 1e-3),
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": None},
+        "kernels": kernels,
+    }
+
+    if a.variants:
+        out["variants"] = time_variants(torch, mx, synth, x8, s, q, sf, a)
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(x8, s, min(a.cpu_sample_rows, M))
+    print(json.dumps(out))
+
+
+def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
+    """Gathered quant (top-8 dispatch emulation), per-token records, grouped row->col."""
+    dev = x8.device
+    M, K = x8.shape
+    res = {}
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    top_k = 8
+    idx = synth.routing_indices(seed=a.seed, num_tokens=M, top_k=top_k, device=dev)
+    Mo = idx.shape[0]
+    qg = torch.empty((Mo, K // 2), dtype=torch.uint8, device=dev)
+    sg = torch.empty((Mo, K // 32), dtype=torch.uint8, device=dev)
+    us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=qg, sf=sg))
+    logical = Mo * K * BYTES_PER_ELEM["quant"]
+    compulsory = M * K * 1.03125 + Mo * 4 + Mo * K * 0.53125
+    res["quant_gather_top8"] = {"us": us, "logical_GB/s": logical / us * 1e-3,
+                                "compulsory_GB/s": compulsory / us * 1e-3,
+                                "frac_of_hbm_peak_compulsory": compulsory / us * 1e-3 / HBM_PEAK_GBPS}
+    rec = K // 2 + K // 32
+    buf = torch.empty(Mo * rec, dtype=torch.uint8, device=dev)
+    us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec))
+    res["quant_gather_top8_records"] = {"us": us, "compulsory_GB/s": compulsory / us * 1e-3}
+    del qg, sg, buf
+    off, _ = synth.expert_offsets(seed=a.seed, num_experts=32, total_tokens=M - 32 * 128, pad_to=128)
+    Mt = int(off[-1])
+    if Mt <= M:
+        offd = off.to(dev)
+        qc = torch.empty(Mt * K // 2, dtype=torch.uint8, device=dev)
+        scc = torch.empty(Mt * K // 32, dtype=torch.uint8, device=dev)
+        us = timed(lambda: mx.mxfp4_row_to_col_grouped(q[:Mt], sf[:Mt], offd, q_col=qc, sf_col=scc))
+        b = Mt * K * BYTES_PER_ELEM["row_to_col"]
+        res["row_to_col_grouped_32_experts"] = {"rows": Mt, "us": us, "GB/s": b / us * 1e-3,
+                                                "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -1,11 +1,11 @@
-"""Run the (single-threaded) oracle over row ranges in a thread pool.  Rows are independent
+"""TEST INFRASTRUCTURE (see ref.py).  Run the (single-threaded) oracle over row ranges in a thread pool.  Rows are independent
 for quant / dequant, 32-row groups for row->col; ctypes releases the GIL during the calls."""
 import os
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
-from oracle import ref
+from . import ref
 
 WORKERS = max(1, min(16, os.cpu_count() or 1))
 

@@ -11,7 +11,7 @@ import torch
 import paper_2603_02731_amd as mx
 from oracle import ref
 from paper_2603_02731_amd import synth
-from tests import par
+from oracle import parallel as par
 from tests.test_oracle_quant import scale_sweep
 
 pytestmark = pytest.mark.gpu
