@@ -64,7 +64,8 @@ enum {
  *              (quantization placed right before the dispatch: the routing gather is fused).
  *   q          packed E2M1, M_out rows of K/2 bytes, row stride ld_q bytes (>= K/2);
  *              pointer and stride 8-byte aligned
- *   sf         UE8M0, M_out rows of K/32 bytes, row stride ld_sf bytes (>= K/32)
+ *   sf         UE8M0, M_out rows of K/32 bytes, row stride ld_sf bytes (>= K/32);
+ *              pointer and stride 4-byte aligned
  * Dense outputs: ld_q = K/2, ld_sf = K/32.  One record per token (nibbles then scales):
  * ld_q = ld_sf = K/2 + K/32, sf = q + K/2. */
 mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,

@@ -13,8 +13,9 @@
 //             constant table built at compile time.
 // The E2M1 codes 0 (zero) and 1 (the subnormal 0.5 = 1.0 * 2^-1) have their own entries.
 //
-// Work split: one lane owns one 1x32 block (16-byte load, 32 bytes stored); the four lanes
-// of a quad own a 128-tile and agree on max(SF) with two DPP exchanges.
+// Work split: one lane owns half a 1x32 block (8-byte load, one 16-byte store), so a wave's
+// loads and stores are contiguous; the 8 lanes of a 128-tile agree on max(SF) with two DPP
+// exchanges.
 // HBM-bound: 0.53125 B read + 1.03125 B written per element.
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
@@ -22,6 +23,7 @@
 namespace mxfp4 {
 
 constexpr int DEQUANT_THREADS = 256;
+constexpr int DEQUANT_UNROLL = 2;
 
 // E4M3 magnitude byte of e2m1(code) * 2^(6-d) for d in [12, 19], rounded to nearest-even.
 // e2m1(code) = h/2 with h below; in units of the E4M3 subnormal quantum 2^-9 the value is
@@ -79,86 +81,96 @@ struct DequantArgs {
     float *x_scale;
     int64_t ld_q;
     int64_t ld_sf;
-    uint32_t n_blocks;       // M * K / 32
-    uint32_t blocks_per_row; // K / 32
+    uint32_t n_halves;      // M * K / 16
+    uint32_t halves_per_row; // K / 16
 };
 
+// One workgroup covers DEQUANT_UNROLL runs of 256 consecutive half-blocks; a lane takes
+// half-block `tid` of each run: 512 B loaded and 1 KiB stored per wave instruction, both
+// contiguous, which is what lets the stores go out non-temporally at full rate.
 template <bool DENSE>
 __global__ void __launch_bounds__(DEQUANT_THREADS) dequant_to_fp8_kernel(const DequantArgs a)
 {
-    const uint32_t c = blockIdx.x * DEQUANT_THREADS + threadIdx.x;
-    if (c >= a.n_blocks)
-        return; // n_blocks is a multiple of 4: a quad exits together
+    const uint32_t c0 = blockIdx.x * (DEQUANT_THREADS * DEQUANT_UNROLL) + threadIdx.x;
 
-    const uint8_t *src;
-    const uint8_t *src_sf;
-    if (DENSE) {
-        src = a.q + (size_t)c * 16;
-        src_sf = a.sf + c;
-    } else {
-        const uint32_t row = c / a.blocks_per_row;
-        const uint32_t cb = c - row * a.blocks_per_row;
-        src = a.q + (size_t)row * a.ld_q + (size_t)cb * 16;
-        src_sf = a.sf + (size_t)row * a.ld_sf + cb;
-    }
-    const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-    const uint32_t b = *src_sf;
-
-    // max over the tile's non-NaN scale bytes, and whether any of them is NaN
-    const uint32_t is_nan = b == 255u ? 1u : 0u;
-    uint32_t bmax = is_nan ? 0u : b;
-    uint32_t any_nan = is_nan;
-    bmax = max(bmax, quad_swap<DPP_QUAD_XOR1>(bmax));
-    any_nan |= quad_swap<DPP_QUAD_XOR1>(any_nan);
-    bmax = max(bmax, quad_swap<DPP_QUAD_XOR2>(bmax));
-    any_nan |= quad_swap<DPP_QUAD_XOR2>(any_nan);
-
-    // the block's 8-entry table: magnitude code -> E4M3 magnitude byte
-    const uint32_t d = bmax - (is_nan ? bmax : b);
-    uint32_t t_lo, t_hi;
-    if (d <= 11u) {
-        t_lo = 0x6c686000u - d * 0x08080800u; // 0, 2^5, 2^6, 1.5*2^6 in E4M3, minus d binades
-        t_hi = 0x7c787470u - d * 0x08080808u; // 2^7, 1.5*2^7, 2^8, 1.5*2^8
-    } else {
-        const uint32_t i = min(d - 12u, 7u);
-        t_lo = c_underflow.lo[i];
-        t_hi = c_underflow.hi[i];
-    }
-    uint32_t sign_even = 0x08080808u, sign_odd = 0x80808080u;
-    if (is_nan) { // a NaN scale byte: the block's 32 outputs are the E4M3 NaN 0x7F
-        t_lo = t_hi = 0x7f7f7f7fu;
-        sign_even = sign_odd = 0u;
-    }
-
-    u32x4 o0, o1;
+    u32x2 w[DEQUANT_UNROLL];
+    uint32_t sfb[DEQUANT_UNROLL];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t wj = w[j];
-        const uint32_t mag_even = perm(t_hi, t_lo, wj & 0x07070707u);
-        const uint32_t mag_odd = perm(t_hi, t_lo, (wj >> 4) & 0x07070707u);
-        const uint32_t even = mag_even | ((wj & sign_even) << 4);
-        const uint32_t odd = mag_odd | (wj & sign_odd);
-        const uint32_t first = perm(odd, even, 0x05010400u);  // elements 0..3 of this dword
-        const uint32_t second = perm(odd, even, 0x07030602u); // elements 4..7
-        if (j < 2) {
-            o0[2 * j] = first;
-            o0[2 * j + 1] = second;
+    for (int u = 0; u < DEQUANT_UNROLL; ++u) {
+        const uint32_t c = c0 + u * DEQUANT_THREADS;
+        if (c >= a.n_halves)
+            break; // n_halves is a multiple of 8: the 8 lanes of a tile leave together
+        const uint8_t *src;
+        const uint8_t *src_sf;
+        if (DENSE) {
+            src = a.q + (size_t)c * 8;
+            src_sf = a.sf + (c >> 1);
         } else {
-            o1[2 * (j - 2)] = first;
-            o1[2 * (j - 2) + 1] = second;
+            const uint32_t row = c / a.halves_per_row;
+            const uint32_t ch = c - row * a.halves_per_row;
+            src = a.q + (size_t)row * a.ld_q + (size_t)ch * 8;
+            src_sf = a.sf + (size_t)row * a.ld_sf + (ch >> 1);
         }
+        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
+        sfb[u] = *src_sf;
     }
-    u32x4 *dst = reinterpret_cast<u32x4 *>(a.x + (size_t)c * 32);
-    dst[0] = o0;
-    dst[1] = o1;
 
-    if ((threadIdx.x & 3u) == 0u) {
-        // 2^(bmax - 6 - 127): the byte goes straight into the FP32 exponent field; below
-        // exponent field 1 the same power of two is an FP32 subnormal.
-        const int b8 = (int)bmax - 6;
-        uint32_t bits = b8 >= 1 ? (uint32_t)b8 << 23 : 0x00400000u >> (uint32_t)(-b8);
-        bits = any_nan ? 0x7fc00000u : bits;
-        a.x_scale[c >> 2] = u2f(bits);
+#pragma unroll
+    for (int u = 0; u < DEQUANT_UNROLL; ++u) {
+        const uint32_t c = c0 + u * DEQUANT_THREADS;
+        if (c >= a.n_halves)
+            break;
+        const uint32_t b = sfb[u];
+
+        // max over the tile's non-NaN scale bytes, and whether any of them is NaN.  Lanes
+        // 2j, 2j+1 of the tile's 8 hold block j: mirroring the 8 pairs block j with block 3-j,
+        // swapping quad halves pairs the two results.
+        const uint32_t is_nan = b == 255u ? 1u : 0u;
+        uint32_t bmax = is_nan ? 0u : b;
+        uint32_t any_nan = is_nan;
+        bmax = max(bmax, dpp_read<DPP_ROW_HALF_MIRROR>(bmax));
+        any_nan |= dpp_read<DPP_ROW_HALF_MIRROR>(any_nan);
+        bmax = max(bmax, dpp_read<DPP_QUAD_XOR2>(bmax));
+        any_nan |= dpp_read<DPP_QUAD_XOR2>(any_nan);
+
+        // the block's 8-entry table: magnitude code -> E4M3 magnitude byte
+        const uint32_t d = bmax - (is_nan ? bmax : b);
+        uint32_t t_lo, t_hi;
+        if (d <= 11u) {
+            t_lo = 0x6c686000u - d * 0x08080800u; // 0, 2^5, 2^6, 1.5*2^6 in E4M3, minus d binades
+            t_hi = 0x7c787470u - d * 0x08080808u; // 2^7, 1.5*2^7, 2^8, 1.5*2^8
+        } else {
+            const uint32_t i = min(d - 12u, 7u);
+            t_lo = c_underflow.lo[i];
+            t_hi = c_underflow.hi[i];
+        }
+        uint32_t sign_even = 0x08080808u, sign_odd = 0x80808080u;
+        if (is_nan) { // a NaN scale byte: the block's 32 outputs are the E4M3 NaN 0x7F
+            t_lo = t_hi = 0x7f7f7f7fu;
+            sign_even = sign_odd = 0u;
+        }
+
+        u32x4 o;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t wj = w[u][j];
+            const uint32_t mag_even = perm(t_hi, t_lo, wj & 0x07070707u);
+            const uint32_t mag_odd = perm(t_hi, t_lo, (wj >> 4) & 0x07070707u);
+            const uint32_t even = mag_even | ((wj & sign_even) << 4);
+            const uint32_t odd = mag_odd | (wj & sign_odd);
+            o[2 * j] = perm(odd, even, 0x05010400u);     // elements 0..3 of this dword
+            o[2 * j + 1] = perm(odd, even, 0x07030602u); // elements 4..7
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.x + (size_t)c * 16));
+
+        if ((threadIdx.x & 7u) == 0u) {
+            // 2^(bmax - 6 - 127): the byte goes straight into the FP32 exponent field; below
+            // exponent field 1 the same power of two is an FP32 subnormal.
+            const int b8 = (int)bmax - 6;
+            uint32_t bits = b8 >= 1 ? (uint32_t)b8 << 23 : 0x00400000u >> (uint32_t)(-b8);
+            bits = any_nan ? 0x7fc00000u : bits;
+            a.x_scale[c >> 3] = u2f(bits);
+        }
     }
 }
 
@@ -172,9 +184,10 @@ hipError_t launch_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *
     a.x_scale = x_scale;
     a.ld_q = ld_q;
     a.ld_sf = ld_sf;
-    a.n_blocks = (uint32_t)(M * (K / 32));
-    a.blocks_per_row = (uint32_t)(K / 32);
-    const uint32_t blocks = (a.n_blocks + DEQUANT_THREADS - 1) / DEQUANT_THREADS;
+    a.n_halves = (uint32_t)(M * (K / 16));
+    a.halves_per_row = (uint32_t)(K / 16);
+    constexpr uint32_t per_block = DEQUANT_THREADS * DEQUANT_UNROLL;
+    const uint32_t blocks = (a.n_halves + per_block - 1) / per_block;
     const bool dense = ld_q == K / 2 && ld_sf == K / 32;
     if (dense)
         hipLaunchKernelGGL(dequant_to_fp8_kernel<true>, dim3(blocks), dim3(DEQUANT_THREADS), 0, stream, a);

@@ -9,7 +9,7 @@ inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 
 inline mxfp4_status launched(hipError_t e) { return e == hipSuccess ? MXFP4_OK : MXFP4_ERR_LAUNCH; }
 
-constexpr int64_t kMaxWorkItems = (int64_t)1 << 32; // kernels index their work with 32 bits
+constexpr int64_t kMaxWorkItems = ((int64_t)1 << 32) - 4096; // kernels index their work with 32 bits
 constexpr int64_t kMaxRows = (int64_t)1 << 31;
 
 } // namespace
@@ -33,8 +33,8 @@ mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_
     if (ld_q < K / 2 || ld_sf < K / 32 || M_src >= kMaxRows || M_out >= kMaxRows || K >= kMaxRows ||
         M_out * (K / 16) >= kMaxWorkItems)
         return MXFP4_ERR_SHAPE;
-    if (!aligned(x, 16) || !aligned(x_scale, 4) || !aligned(q, 8) || ld_q % 8 != 0 ||
-        (gather_idx && !aligned(gather_idx, 4)))
+    if (!aligned(x, 16) || !aligned(x_scale, 4) || !aligned(q, 8) || ld_q % 8 != 0 || !aligned(sf, 4) ||
+        ld_sf % 4 != 0 || (gather_idx && !aligned(gather_idx, 4)))
         return MXFP4_ERR_ALIGN;
     return launched(mxfp4::launch_quant_from_fp8(x, x_scale, M_src, K, gather_idx, M_out, q, ld_q, sf, ld_sf,
                                                  static_cast<hipStream_t>(hip_stream)));
@@ -49,7 +49,7 @@ mxfp4_status mxfp4_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t 
         return MXFP4_OK;
     if (!q || !sf || !x || !x_scale)
         return MXFP4_ERR_NULL;
-    if (ld_q < K / 2 || ld_sf < K / 32 || M >= kMaxRows || K >= kMaxRows || M * (K / 32) >= kMaxWorkItems)
+    if (ld_q < K / 2 || ld_sf < K / 32 || M >= kMaxRows || K >= kMaxRows || M * (K / 16) >= kMaxWorkItems)
         return MXFP4_ERR_SHAPE;
     if (!aligned(q, 16) || ld_q % 16 != 0 || !aligned(x, 16) || !aligned(x_scale, 4))
         return MXFP4_ERR_ALIGN;

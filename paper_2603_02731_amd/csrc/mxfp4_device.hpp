@@ -33,14 +33,21 @@ __device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel)
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
-// Value of the lane whose index differs in bit 0 / bit 1 (within a quad), by DPP.
+// Value of another lane of the same row of 16, selected by a DPP control.
 template <int CTRL>
-__device__ __forceinline__ uint32_t quad_swap(uint32_t v)
+__device__ __forceinline__ uint32_t dpp_read(uint32_t v)
 {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 constexpr int DPP_QUAD_XOR1 = 0xB1; // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_XOR2 = 0x4E; // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> lane 7-i inside each group of 8
+
+// Value of lane i+4 of the same row of 16 lanes (0 where there is none), by DPP.
+__device__ __forceinline__ uint32_t row_shift_left4(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104 /* row_shl:4 */, 0xF, 0xF, true);
+}
 
 // NaN-propagating maximum of |a|, |b| and c.
 __device__ __forceinline__ float max3_abs_nan(float a, float b, float c)

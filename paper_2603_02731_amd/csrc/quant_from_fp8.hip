@@ -9,7 +9,8 @@
 //   16 B load -> 8 x v_cvt_pk_f32_fp8 -> 16 x v_mul_f32 (the one FP32 rounding)
 //   -> NaN-propagating |max| (v_maximum3_f32) -> one DPP exchange with the pair lane
 //   -> exponent-field arithmetic for the UE8M0 byte -> 8 x v_cvt_scalef32_pk_fp4_f32
-//   -> one 8-byte store of 16 nibbles; the even lane of a pair stores the scale byte.
+//   -> one 8-byte store of 16 nibbles; the tile's four scale bytes are gathered by DPP
+//      into lane 0 of its 8 lanes and leave as one dword.
 // HBM-bound: 1.03125 B read + 0.53125 B written per element.
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
@@ -17,6 +18,7 @@
 namespace mxfp4 {
 
 constexpr int QUANT_THREADS = 256;
+constexpr int QUANT_UNROLL = 2;
 
 struct QuantArgs {
     const uint8_t *x;
@@ -51,7 +53,7 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
 #pragma unroll
     for (int j = 0; j < 16; j += 2)
         m = max3_abs_nan(v[j], v[j + 1], m);
-    float other = u2f(quad_swap<DPP_QUAD_XOR1>(f2u(m)));
+    float other = u2f(dpp_read<DPP_QUAD_XOR1>(f2u(m)));
     m = __builtin_elementwise_maximum(m, other);
 
     uint32_t b = ue8m0_of_block_max(f2u(m));
@@ -71,52 +73,68 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
     *scale_byte = b;
 }
 
+// One workgroup covers QUANT_UNROLL runs of 256 consecutive chunks; a lane takes chunk
+// `tid` of each run, so every load and store instruction of a wave stays contiguous
+// (1 KiB in, 512 B out) while each lane keeps QUANT_UNROLL loads in flight.
 // DENSE: no gather and dense outputs -- every address is a multiple of the flat chunk index.
 template <bool DENSE>
 __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const QuantArgs a)
 {
-    const uint32_t c = blockIdx.x * QUANT_THREADS + threadIdx.x;
-    if (c >= a.n_chunks)
-        return; // n_chunks is a multiple of 8, so the two lanes of a pair exit together
+    const uint32_t c0 = blockIdx.x * (QUANT_THREADS * QUANT_UNROLL) + threadIdx.x;
 
-    const uint8_t *src;
-    const float *src_scale;
-    uint8_t *dst_q;
-    uint8_t *dst_sf;
-    bool valid = true;
-    if (DENSE) {
-        src = a.x + (size_t)c * 16;
-        src_scale = a.x_scale + (c >> 3);
-        dst_q = a.q + (size_t)c * 8;
-        dst_sf = a.sf + (c >> 1);
-    } else {
-        const uint32_t row = c / a.chunks_per_row;
-        const uint32_t cc = c - row * a.chunks_per_row;
-        uint32_t src_row = row;
-        if (a.gather_idx) {
-            src_row = (uint32_t)a.gather_idx[row];
-            valid = src_row < a.M_src; // also rejects negative indices
-            src_row = valid ? src_row : 0u;
+    u32x4 w[QUANT_UNROLL];
+    float s[QUANT_UNROLL];
+    uint8_t *dst_q[QUANT_UNROLL];
+    uint8_t *dst_sf[QUANT_UNROLL]; // the tile's four scale bytes (one aligned dword)
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        const uint32_t c = c0 + u * QUANT_THREADS;
+        if (c >= a.n_chunks)
+            break; // n_chunks is a multiple of 8: the 8 lanes of a tile leave together
+        const uint8_t *src;
+        const float *src_scale;
+        bool valid = true;
+        if (DENSE) {
+            src = a.x + (size_t)c * 16;
+            src_scale = a.x_scale + (c >> 3);
+            dst_q[u] = a.q + (size_t)c * 8;
+            dst_sf[u] = a.sf + (size_t)(c >> 3) * 4;
+        } else {
+            const uint32_t row = c / a.chunks_per_row;
+            const uint32_t cc = c - row * a.chunks_per_row;
+            uint32_t src_row = row;
+            if (a.gather_idx) {
+                src_row = (uint32_t)a.gather_idx[row];
+                valid = src_row < a.M_src; // also rejects negative indices
+                src_row = valid ? src_row : 0u;
+            }
+            src = a.x + (size_t)src_row * a.K + (size_t)cc * 16;
+            src_scale = a.x_scale + (size_t)src_row * (a.K >> 7) + (cc >> 3);
+            dst_q[u] = a.q + (size_t)row * a.ld_q + (size_t)cc * 8;
+            dst_sf[u] = a.sf + (size_t)row * a.ld_sf + (size_t)(cc >> 3) * 4;
         }
-        src = a.x + (size_t)src_row * a.K + (size_t)cc * 16;
-        src_scale = a.x_scale + (size_t)src_row * (a.K >> 7) + (cc >> 3);
-        dst_q = a.q + (size_t)row * a.ld_q + (size_t)cc * 8;
-        dst_sf = a.sf + (size_t)row * a.ld_sf + (cc >> 1);
+        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        s[u] = *src_scale;
+        if (!valid) { // an out-of-range gather index yields a zero row
+            w[u] = u32x4{0u, 0u, 0u, 0u};
+            s[u] = 0.0f;
+        }
     }
 
-    u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-    float s = *src_scale;
-    if (!valid) {
-        w = u32x4{0u, 0u, 0u, 0u};
-        s = 0.0f;
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        if (c0 + u * QUANT_THREADS >= a.n_chunks)
+            break;
+        uint32_t out[2], b;
+        quant16(w[u], s[u], out, &b);
+        __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
+
+        // lanes 2j, 2j+1 of the tile's 8 hold block j's byte: gather the four into lane 0
+        uint32_t t = b | (dpp_read<DPP_QUAD_XOR2>(b) << 8); // lanes 0,1: B0 | B1 << 8
+        t |= row_shift_left4(t) << 16;                       // lane 0: ... | B2 << 16 | B3 << 24
+        if ((threadIdx.x & 7u) == 0u)
+            *reinterpret_cast<uint32_t *>(dst_sf[u]) = t;
     }
-
-    uint32_t out[2], b;
-    quant16(w, s, out, &b);
-
-    __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q));
-    if ((threadIdx.x & 1u) == 0u)
-        *dst_sf = (uint8_t)b;
 }
 
 hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
@@ -135,7 +153,8 @@ hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t
     a.chunks_per_row = (uint32_t)(K / 16);
     a.K = (uint32_t)K;
     a.M_src = (uint32_t)M_src;
-    const uint32_t blocks = (a.n_chunks + QUANT_THREADS - 1) / QUANT_THREADS;
+    constexpr uint32_t per_block = QUANT_THREADS * QUANT_UNROLL;
+    const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
     const bool dense = gather_idx == nullptr && ld_q == K / 2 && ld_sf == K / 32;
     if (dense)
         hipLaunchKernelGGL(quant_from_fp8_kernel<true>, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);

@@ -24,6 +24,15 @@
 
 namespace mxfp4 {
 
+#ifndef MXFP4_RTC_GRID
+#define MXFP4_RTC_GRID 0
+#endif
+#ifndef MXFP4_RTC_NT
+#define MXFP4_RTC_NT 0
+#endif
+#ifndef MXFP4_RTC_WAVES
+#define MXFP4_RTC_WAVES 1
+#endif
 constexpr int T_THREADS = 256;
 constexpr int TILE_M = 256;
 constexpr int TILE_K = 256;
@@ -158,14 +167,14 @@ __device__ __noinline__ void requant_slice_int(const uint8_t *src, size_t src_pi
     }
 }
 
-__global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArgs a)
+__global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
 {
     __shared__ u32x4 s_out[TILE_K * 8];                   // [c*32 + cg][slot]: 256 k-rows x 128 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
     __shared__ alignas(16) uint8_t s_col_sf[TILE_K * 8]; // [k][row group]
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
-    uint32_t row_base = 0, rows = a.M, tile = blockIdx.y;
+    uint32_t row_base = 0, rows = a.M, tile = MXFP4_RTC_GRID ? blockIdx.x : blockIdx.y;
     if (a.expert_offsets) {
         bool found = false;
         for (int e = 0; e < a.num_experts; ++e) {
@@ -186,7 +195,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
     if (m0 >= rows)
         return;
     const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
-    const uint32_t k0 = blockIdx.x * TILE_K;
+    const uint32_t k0 = (MXFP4_RTC_GRID ? blockIdx.y : blockIdx.x) * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
 
@@ -274,7 +283,10 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
         const uint32_t part = (slot - (cgx >> 1)) & 7u; // row group held in this slot
         if (k < cols && part < n_rg) {
             u32x4 *dst = reinterpret_cast<u32x4 *>(out_q + (size_t)(k0 + k) * pitch_q + m0 / 2u + part * 16u);
-            *dst = s_out[f];
+            if (MXFP4_RTC_NT)
+                __builtin_nontemporal_store(s_out[f], dst);
+            else
+                *dst = s_out[f];
         }
     }
     if (tid < cols) {
@@ -305,7 +317,9 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.K = (uint32_t)K;
     // upper bound on the number of 256-row tiles: every expert may end in a partial tile
     const int64_t m_tiles = (M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0);
-    const dim3 grid((uint32_t)((K + TILE_K - 1) / TILE_K), (uint32_t)m_tiles);
+    const dim3 grid_km((uint32_t)((K + TILE_K - 1) / TILE_K), (uint32_t)m_tiles);
+    const dim3 grid_mk((uint32_t)m_tiles, (uint32_t)((K + TILE_K - 1) / TILE_K));
+    const dim3 grid = MXFP4_RTC_GRID ? grid_mk : grid_km;
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
 }
