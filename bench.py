@@ -29,6 +29,9 @@ def parse():
     p.add_argument("--seed", type=int, default=0)
     p.add_argument("--cpu-sample-rows", type=int, default=32768)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="run only plain device copies of a known size (512 MiB read + 512 MiB written per "
+                        "launch): the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
     p.add_argument("--variants", action="store_true",
                    help="also time the gathered, record-layout and grouped entry points (extra JSON field)")
     return p.parse_args()
@@ -58,6 +61,20 @@ def cpu_baseline(x8, s, rows):
     }
 
 
+def measured_traffic(kernel, M, K):
+    """HBM bytes per launch of `kernel` as rocprofv3 counted them (profiles/hbm_traffic.json), or None
+    when no counter run covers this workload."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    try:
+        t = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if t.get("workload") != f"target_{M}x{K}" or kernel not in t.get("kernels", {}):
+        return None
+    k = t["kernels"][kernel]
+    return k["read"] + k["written"]
+
+
 def main():
     a = parse()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -75,6 +92,17 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     mx.lib()  # fail loudly here if the HIP library is missing
+
+    if a.copy_calibration:
+        n = 512 << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(a.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": a.steps, "bytes_read_per_launch": n,
+                          "bytes_written_per_launch": n}))
+        return
 
     M, K = a.rows, a.hidden
     x8, s = synth.student_t_fp8(M, K, seed=a.seed, device=dev)
@@ -120,6 +148,7 @@ def main():
     total_bytes = n * sum(BYTES_PER_ELEM.values())
     value = total_bytes / (ms_per_step * 1e-3) * 1e-9
     dom = max(names, key=lambda k: kernels[k]["us"])
+    traffic = measured_traffic(dom, M, K)
 
     out = {
         "metric": "HBM GB/s (% of peak) for FP8<->MXFP4 quant/dequant and MXFP4 row->col",
@@ -132,7 +161,7 @@ def main():
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
         "elements_per_s": 3 * n / (ms_per_step * 1e-3),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": None},
+                     "unit": "GB/s", "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": traffic},
         "kernels": kernels,
     }
 
