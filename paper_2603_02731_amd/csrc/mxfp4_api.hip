@@ -67,9 +67,9 @@ static mxfp4_status row_to_col_common(const uint8_t *q_row, const uint8_t *sf_ro
         return MXFP4_OK;
     if (!q_row || !sf_row || !q_col || !sf_col)
         return MXFP4_ERR_NULL;
-    // grid.y holds one entry per 256-row tile (plus one per expert), grid.y <= 65535;
-    // byte offsets inside a 256-row tile are 32-bit
-    if (M >= kMaxRows || K > ((int64_t)1 << 24) || (M + 255) / 256 + num_experts > 65535)
+    // byte offsets inside a 256-row tile are 32-bit, and so is the tile count
+    if (M >= kMaxRows || K > ((int64_t)1 << 24) ||
+        ((M + 255) / 256 + num_experts) * ((K + 255) / 256) >= ((int64_t)1 << 31))
         return MXFP4_ERR_SHAPE;
     if (!aligned(q_row, 4) || !aligned(sf_row, 4) || !aligned(q_col, 16) ||
         (expert_offsets && !aligned(expert_offsets, 4)))

@@ -18,17 +18,18 @@
 //           the 32x32 block, no nibble shuffling is needed.
 // The 8 x 16 B per lane then go through an LDS tile (swizzled so that both the 16-byte
 // writes and the linear read-back are bank-conflict free) to leave as full 128-byte rows.
-// HBM-bound: 0.53125 B read + 0.53125 B written per element.
+// Workgroups take their tiles in an XCD-aware order (tile_of_workgroup), which is what keeps
+// the HBM traffic at the algorithmic 0.53125 B read + 0.53125 B written per element.
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
 namespace mxfp4 {
 
-#ifndef MXFP4_RTC_GRID
-#define MXFP4_RTC_GRID 0
+#ifndef MXFP4_RTC_MBM
+#define MXFP4_RTC_MBM 32
 #endif
-#ifndef MXFP4_RTC_NT
-#define MXFP4_RTC_NT 0
+#ifndef MXFP4_RTC_MBK
+#define MXFP4_RTC_MBK 4
 #endif
 #ifndef MXFP4_RTC_WAVES
 #define MXFP4_RTC_WAVES 1
@@ -46,13 +47,45 @@ struct RowToColArgs {
     int32_t num_experts;
     uint32_t M; // total rows
     uint32_t K;
+    uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
+    uint32_t tiles_k; // 256-column tiles
 };
 
-// Byte i%4 of dword i/4.
-template <int I>
-__device__ __forceinline__ uint32_t row_byte(const uint32_t (&sb)[8])
+// Workgroup -> tile.  The hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
+// each with its own L2.  Id i therefore takes entry i/8 of XCD (i%8)'s own contiguous share
+// of a tile order in which MBM x MBK tiles form a macro block walked m-fastest: the tiles an
+// XCD has in flight together are neighbours along m (their 128-byte output pieces and 8-byte
+// column-scale pieces complete whole lines in that L2) and along k (they share the 32-byte
+// sectors of the row scales).
+constexpr uint32_t NUM_XCD = 8, MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK;
+__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
+                                                  uint32_t *tile_m, uint32_t *tile_k)
 {
-    return (sb[I >> 2] >> (8 * (I & 3))) & 0xFFu;
+    const uint32_t total = tiles_m * tiles_k;
+    const uint32_t per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
+    const uint32_t l = (id % NUM_XCD) * per_xcd + id / NUM_XCD;
+    if (id / NUM_XCD >= per_xcd || l >= total)
+        return false;
+    const uint32_t per_macro_row = MBM * tiles_k;
+    const uint32_t mg = l / per_macro_row;
+    const uint32_t rem = l - mg * per_macro_row;
+    const uint32_t mb_rows = min(MBM, tiles_m - mg * MBM);
+    const uint32_t kg = rem / (MBK * mb_rows);
+    const uint32_t rem2 = rem - kg * MBK * mb_rows;
+    const uint32_t k_in = rem2 / mb_rows;
+    *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
+    *tile_k = kg * MBK + k_in;
+    return true;
+}
+
+// Scale operand of row I of a slice: its UE8M0 byte (byte I%4 of dword I/4) moved into bits
+// 30:23 with one shift.  What lands in the sign and mantissa bits belongs to the neighbouring
+// bytes; the conversion instructions read the exponent field only.
+template <int I>
+__device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
+{
+    constexpr int j = I & 3;
+    return u2f(j == 3 ? sb[I >> 2] >> 1 : sb[I >> 2] << (23 - 8 * j));
 }
 
 // One lane's 32x8 slice through the hardware conversions.  Exact while every value
@@ -61,15 +94,14 @@ __device__ __forceinline__ uint32_t row_byte(const uint32_t (&sb)[8])
 __device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&sb)[8], uint32_t (&cb)[8],
                                                  uint32_t (&o)[8][4])
 {
-    // pass 1: column maxima of |value|.  The scale operand of a row is its byte moved into
-    // the FP32 exponent field; it is rebuilt where it is used rather than kept in 32 registers.
+    // pass 1: column maxima of |value| (no NaN can occur: NaN row scales never get here)
     float amax[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c)
         amax[c] = 0.0f;
     static_for<16>([&](auto ip) {
         constexpr int i = 2 * decltype(ip)::value;
-        const float sa = u2f(row_byte<i>(sb) << 23), sbb = u2f(row_byte<i + 1>(sb) << 23);
+        const float sa = row_scale_operand<i>(sb), sbb = row_scale_operand<i + 1>(sb);
         static_for<4>([&](auto jp) {
             constexpr int j = decltype(jp)::value;
             const f32x2 fa = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sa, j);
@@ -79,11 +111,13 @@ __device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&s
         });
     });
 
-    // column scales (sec. 3.1 rule on the exponent field)
+    // column scales: the sec. 3.1 rule on the exponent field.  A maximum with at most two
+    // significant bits (1.0 or 1.5 times a power of two) never exceeds 1.5 * 2^e, so the byte
+    // is its exponent field minus 2, clamped at 0; zero and FP32 subnormals give 0.
     float cs[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-        cb[c] = ue8m0_of_block_max(f2u(amax[c]));
+        cb[c] = max(f2u(amax[c]) >> 23, 2u) - 2u;
         cs[c] = u2f(cb[c] << 23);
     }
 
@@ -105,11 +139,11 @@ __device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&s
     for (int c = 0; c < 8; ++c)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            o[c][g] = 0u;
+            asm volatile("" : "=v"(o[c][g])); // no initial value needed: all four bytes are written
     static_for<16>([&](auto ip) {
         constexpr int i = 2 * decltype(ip)::value;
         constexpr int g = i >> 3, sel = (i >> 1) & 3; // output dword and byte of rows (i, i+1)
-        const float sa = u2f(row_byte<i>(sb) << 23), sbb = u2f(row_byte<i + 1>(sb) << 23);
+        const float sa = row_scale_operand<i>(sb), sbb = row_scale_operand<i + 1>(sb);
         static_for<4>([&](auto jp) {
             constexpr int j = decltype(jp)::value;
             const f32x2 fa = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sa, j);
@@ -172,9 +206,14 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     __shared__ u32x4 s_out[TILE_K * 8];                   // [c*32 + cg][slot]: 256 k-rows x 128 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
     __shared__ alignas(16) uint8_t s_col_sf[TILE_K * 8]; // [k][row group]
+    __shared__ uint8_t s_special[8];                      // per row group: bit kb set = a scale byte >= 253
+
+    uint32_t tile, tile_k;
+    if (!tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_k, &tile, &tile_k))
+        return;
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
-    uint32_t row_base = 0, rows = a.M, tile = MXFP4_RTC_GRID ? blockIdx.x : blockIdx.y;
+    uint32_t row_base = 0, rows = a.M;
     if (a.expert_offsets) {
         bool found = false;
         for (int e = 0; e < a.num_experts; ++e) {
@@ -195,7 +234,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     if (m0 >= rows)
         return;
     const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
-    const uint32_t k0 = (MXFP4_RTC_GRID ? blockIdx.y : blockIdx.x) * TILE_K;
+    const uint32_t k0 = tile_k * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
 
@@ -205,88 +244,105 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     const size_t pitch_q = rows / 2, pitch_sf = rows / 32;
 
     const uint32_t tid = threadIdx.x;
-
-    // ---- stage the tile's row scales: thread t takes row t, 4 or 8 bytes
-    if (tid < n_rg * 32u) {
-        const uint32_t *p = reinterpret_cast<const uint32_t *>(
-            a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u);
-        const uint32_t lo = p[0];
-        const uint32_t hi = cols > 128u ? p[1] : 0u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
-            s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
-        }
-    }
-    __syncthreads();
-
     const uint32_t rg = tid >> 5, cg = tid & 31u;
     const bool active = rg < n_rg && cg * 8u < cols;
 
+    // ---- load the 32x8 slice: one dword (8 nibbles) per row, issued before anything waits
+    // (a uniform row pointer plus a 32-bit lane offset: one address register, not 32 pairs)
+    uint32_t w[32];
+    const uint32_t pitch = a.K / 2u;
+    const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
+    const uint32_t lane_off = rg * 32u * pitch + cg * 4u; // < 2^32: K is at most 2^24
     if (active) {
-        // ---- load the 32x8 slice: one dword (8 nibbles) per row
-        // (a uniform row pointer plus a 32-bit lane offset: one address register, not 32 pairs)
-        uint32_t w[32];
-        const uint32_t pitch = a.K / 2u;
-        const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
-        const uint32_t lane_off = rg * 32u * pitch + cg * 4u; // < 2^32: K is at most 2^24
 #pragma unroll
         for (int i = 0; i < 32; ++i)
             w[i] = __builtin_nontemporal_load(
                 reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+    }
 
-        // the 32 row-scale bytes of this slice: 8 dwords, byte i%4 of dword i/4 is row i
-        uint32_t sb[8];
-        {
-            const u32x4 *p = reinterpret_cast<const u32x4 *>(&s_row_sf[(cg >> 2) * TILE_M + rg * 32u]);
-            const u32x4 s0 = p[0], s1 = p[1];
+    // ---- stage the tile's row scales: thread t takes row t, 4 or 8 bytes.  A wave stages two
+    // row groups; one ballot per k-block tells which (row group, k-block) pairs hold a byte
+    // of 253 or more (beyond FP32, or NaN).
+    {
+        uint32_t lo = 0, hi = 0;
+        if (tid < n_rg * 32u) {
+            const uint32_t *p = reinterpret_cast<const uint32_t *>(
+                a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u);
+            lo = p[0];
+            hi = cols > 128u ? p[1] : 0u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
+                s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
+            }
+        }
+        uint32_t special_lo = 0, special_hi = 0; // bit kb: first / second row group of this wave
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
+            const uint64_t m = __ballot(b >= 253u);
+            special_lo |= ((uint32_t)m != 0u ? 1u : 0u) << j;
+            special_hi |= ((uint32_t)(m >> 32) != 0u ? 1u : 0u) << j;
+        }
+        if ((tid & 63u) == 0u) {
+            s_special[(tid >> 6) * 2] = (uint8_t)special_lo;
+            s_special[(tid >> 6) * 2 + 1] = (uint8_t)special_hi;
+        }
+    }
+    __syncthreads();
+
+    if (active) {
+        // ---- results go to LDS: row (c*32 + cg), 16-byte slot rotated by cg/2, so that 16
+        // consecutive lanes cover 256 consecutive-bank bytes and the read-back below is linear
+        const uint32_t slot = (rg + (cg >> 1)) & 7u;
+        const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * TILE_M + rg * 32u];
+        if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
+            // the 32 row-scale bytes of this slice: byte i%4 of dword i/4 is row i
+            uint32_t sb[8];
+            const u32x4 s0 = reinterpret_cast<const u32x4 *>(my_row_sf)[0];
+            const u32x4 s1 = reinterpret_cast<const u32x4 *>(my_row_sf)[1];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 sb[g] = s0[g];
                 sb[4 + g] = s1[g];
             }
-        }
-        uint32_t sf_max = 0;
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-            sf_max = max(sf_max, (sb[i >> 2] >> (8 * (i & 3))) & 0xFFu);
-        const bool poisoned = sf_max == 255u; // a NaN row scale touches all 8 columns
-
-        // ---- results go to LDS: row (c*32 + cg), 16-byte slot rotated by cg/2, so that 16
-        // consecutive lanes cover 256 consecutive-bank bytes and the read-back below is linear
-        const uint32_t slot = (rg + (cg >> 1)) & 7u;
-        if (sf_max < 253u || poisoned) {
             uint32_t cb[8];   // column scale bytes
             uint32_t o[8][4]; // per column: 32 output nibbles (rows 0..31 of the slice)
             requant_slice_hw(w, sb, cb, o);
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                u32x4 v = poisoned ? u32x4{0u, 0u, 0u, 0u} : u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
-                s_out[(c * 32 + cg) * 8 + slot] = v;
-                s_col_sf[(cg * 8 + c) * 8 + rg] = (uint8_t)(poisoned ? 255u : cb[c]);
+                s_out[(c * 32 + cg) * 8 + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
+                s_col_sf[(cg * 8 + c) * 8 + rg] = (uint8_t)cb[c];
             }
         } else {
-            requant_slice_int(tile_src + lane_off, pitch, &s_row_sf[(cg >> 2) * TILE_M + rg * 32u],
-                              reinterpret_cast<uint32_t *>(&s_out[cg * 8 + slot]), 32 * 8 * 4,
-                              &s_col_sf[cg * 8 * 8 + rg], 8);
+            bool poisoned = false; // a NaN row scale touches all 8 columns of the slice
+            for (int i = 0; i < 32; ++i)
+                poisoned |= my_row_sf[i] == 255u;
+            if (poisoned) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    s_out[(c * 32 + cg) * 8 + slot] = u32x4{0u, 0u, 0u, 0u};
+                    s_col_sf[(cg * 8 + c) * 8 + rg] = 255u;
+                }
+            } else {
+                requant_slice_int(tile_src + lane_off, pitch, my_row_sf,
+                                  reinterpret_cast<uint32_t *>(&s_out[cg * 8 + slot]), 32 * 8 * 4,
+                                  &s_col_sf[cg * 8 * 8 + rg], 8);
+            }
         }
     }
     __syncthreads();
 
-    // ---- write the tile out: 8 lanes per k-row, 128 contiguous bytes each
+    // ---- write the tile out: 8 lanes per k-row, 128 contiguous bytes each.  Chunk f = u*256 +
+    // tid of the LDS tile is row (u*32 + tid/8), slot tid%8: column k = (tid/8)*8 + u.
+    {
+        const uint32_t cgx = tid >> 3;
+        const uint32_t part = ((tid & 7u) - (cgx >> 1)) & 7u; // row group held in this slot
+        uint8_t *dst = out_q + (size_t)(k0 + cgx * 8u) * pitch_q + m0 / 2u + part * 16u;
+        if (cgx * 8u < cols && part < n_rg) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const uint32_t f = u * T_THREADS + tid;
-        const uint32_t r = f >> 3, slot = f & 7u;
-        const uint32_t cgx = r & 31u, c = r >> 5;
-        const uint32_t k = cgx * 8u + c;
-        const uint32_t part = (slot - (cgx >> 1)) & 7u; // row group held in this slot
-        if (k < cols && part < n_rg) {
-            u32x4 *dst = reinterpret_cast<u32x4 *>(out_q + (size_t)(k0 + k) * pitch_q + m0 / 2u + part * 16u);
-            if (MXFP4_RTC_NT)
-                __builtin_nontemporal_store(s_out[f], dst);
-            else
-                *dst = s_out[f];
+            for (int u = 0; u < 8; ++u)
+                *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
         }
     }
     if (tid < cols) {
@@ -316,10 +372,10 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.M = (uint32_t)M;
     a.K = (uint32_t)K;
     // upper bound on the number of 256-row tiles: every expert may end in a partial tile
-    const int64_t m_tiles = (M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0);
-    const dim3 grid_km((uint32_t)((K + TILE_K - 1) / TILE_K), (uint32_t)m_tiles);
-    const dim3 grid_mk((uint32_t)m_tiles, (uint32_t)((K + TILE_K - 1) / TILE_K));
-    const dim3 grid = MXFP4_RTC_GRID ? grid_mk : grid_km;
+    a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
+    a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
+    const uint32_t total = a.tiles_m * a.tiles_k;
+    const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
 }
