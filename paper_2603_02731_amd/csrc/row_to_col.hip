@@ -6,7 +6,8 @@
 // the scale rule and rounding of sec. 3.1.
 //
 // Work split.  A workgroup of 256 lanes owns a 256 (m) x 256 (k) tile, the unit that makes
-// both global reads and global writes 128-byte contiguous.  Inside, the unit of work is the
+// both global reads and global writes 128-byte contiguous (512-row tiles with 512 lanes
+// were measured too: fewer scale requests, but slower overall).  Inside, the unit of work is the
 // 32x32 block of the method: lane (rg, cg) owns rows 32*rg..32*rg+31 and the 8 columns
 // 8*cg..8*cg+7, i.e. one 32x8 slice of a 32x32 block, as 32 dwords of nibbles (one per row).
 //   pass 1: v_cvt_scalef32_pk_f32_fp4 (row scale applied by the instruction, two columns
@@ -25,8 +26,11 @@
 
 namespace mxfp4 {
 
+#ifndef MXFP4_RTC_NRG
+#define MXFP4_RTC_NRG 8
+#endif
 #ifndef MXFP4_RTC_MBM
-#define MXFP4_RTC_MBM 32
+#define MXFP4_RTC_MBM (256 / MXFP4_RTC_NRG)
 #endif
 #ifndef MXFP4_RTC_MBK
 #define MXFP4_RTC_MBK 4
@@ -34,9 +38,11 @@ namespace mxfp4 {
 #ifndef MXFP4_RTC_WAVES
 #define MXFP4_RTC_WAVES 1
 #endif
-constexpr int T_THREADS = 256;
-constexpr int TILE_M = 256;
+constexpr int NRG = MXFP4_RTC_NRG;  // 32-row groups per tile
+constexpr int T_THREADS = 32 * NRG; // one lane per (row group, 8-column group)
+constexpr int TILE_M = 32 * NRG;
 constexpr int TILE_K = 256;
+static_assert(NRG == 8 || NRG == 16, "the LDS slot swizzle assumes 8 or 16 row groups");
 
 struct RowToColArgs {
     const uint8_t *q_row;
@@ -47,7 +53,7 @@ struct RowToColArgs {
     int32_t num_experts;
     uint32_t M; // total rows
     uint32_t K;
-    uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
+    uint32_t tiles_m; // row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
 };
 
@@ -203,10 +209,10 @@ __device__ __noinline__ void requant_slice_int(const uint8_t *src, size_t src_pi
 
 __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
 {
-    __shared__ u32x4 s_out[TILE_K * 8];                   // [c*32 + cg][slot]: 256 k-rows x 128 B
-    __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
-    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * 8]; // [k][row group]
-    __shared__ uint8_t s_special[8];                      // per row group: bit kb set = a scale byte >= 253
+    __shared__ u32x4 s_out[TILE_K * NRG];                  // [c*32 + cg][slot]: 256 k-rows x NRG*16 B
+    __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M];   // [k-block of the tile][row]
+    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [k][row group]
+    __shared__ uint8_t s_special[NRG];                     // per row group: bit kb set = a scale byte >= 253
 
     uint32_t tile, tile_k;
     if (!tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_k, &tile, &tile_k))
@@ -266,10 +272,16 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     {
         uint32_t lo = 0, hi = 0;
         if (tid < n_rg * 32u) {
-            const uint32_t *p = reinterpret_cast<const uint32_t *>(
-                a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u);
-            lo = p[0];
-            hi = cols > 128u ? p[1] : 0u;
+            // one 8-byte request per row where the layout allows it (K % 256 == 0), else 4 + 4
+            const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
+            if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
+                const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+                lo = v.x;
+                hi = v.y;
+            } else {
+                lo = reinterpret_cast<const uint32_t *>(p)[0];
+                hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
@@ -292,9 +304,9 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     __syncthreads();
 
     if (active) {
-        // ---- results go to LDS: row (c*32 + cg), 16-byte slot rotated by cg/2, so that 16
-        // consecutive lanes cover 256 consecutive-bank bytes and the read-back below is linear
-        const uint32_t slot = (rg + (cg >> 1)) & 7u;
+        // ---- results go to LDS: row (c*32 + cg), 16-byte slot rotated by the column group, so
+        // that consecutive lanes write different banks, and the read-back below is linear
+        const uint32_t slot = (rg + (NRG == 16 ? cg : cg >> 1)) & (NRG - 1u);
         const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * TILE_M + rg * 32u];
         if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
             // the 32 row-scale bytes of this slice: byte i%4 of dword i/4 is row i
@@ -311,8 +323,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             requant_slice_hw(w, sb, cb, o);
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                s_out[(c * 32 + cg) * 8 + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
-                s_col_sf[(cg * 8 + c) * 8 + rg] = (uint8_t)cb[c];
+                s_out[(c * 32 + cg) * NRG + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
+                s_col_sf[(cg * 8 + c) * NRG + rg] = (uint8_t)cb[c];
             }
         } else {
             bool poisoned = false; // a NaN row scale touches all 8 columns of the slice
@@ -321,23 +333,24 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             if (poisoned) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    s_out[(c * 32 + cg) * 8 + slot] = u32x4{0u, 0u, 0u, 0u};
-                    s_col_sf[(cg * 8 + c) * 8 + rg] = 255u;
+                    s_out[(c * 32 + cg) * NRG + slot] = u32x4{0u, 0u, 0u, 0u};
+                    s_col_sf[(cg * 8 + c) * NRG + rg] = 255u;
                 }
             } else {
                 requant_slice_int(tile_src + lane_off, pitch, my_row_sf,
-                                  reinterpret_cast<uint32_t *>(&s_out[cg * 8 + slot]), 32 * 8 * 4,
-                                  &s_col_sf[cg * 8 * 8 + rg], 8);
+                                  reinterpret_cast<uint32_t *>(&s_out[cg * NRG + slot]), 32 * NRG * 4,
+                                  &s_col_sf[cg * 8 * NRG + rg], NRG);
             }
         }
     }
     __syncthreads();
 
-    // ---- write the tile out: 8 lanes per k-row, 128 contiguous bytes each.  Chunk f = u*256 +
-    // tid of the LDS tile is row (u*32 + tid/8), slot tid%8: column k = (tid/8)*8 + u.
+    // ---- write the tile out: NRG lanes per k-row, NRG*16 contiguous bytes each.  Chunk
+    // f = u*T_THREADS + tid of the LDS tile is row (u*32 + tid/NRG), slot tid%NRG: column
+    // k = (tid/NRG)*8 + u.
     {
-        const uint32_t cgx = tid >> 3;
-        const uint32_t part = ((tid & 7u) - (cgx >> 1)) & 7u; // row group held in this slot
+        const uint32_t cgx = tid / NRG;
+        const uint32_t part = ((tid & (NRG - 1u)) - (NRG == 16 ? cgx : cgx >> 1)) & (NRG - 1u); // row group in this slot
         uint8_t *dst = out_q + (size_t)(k0 + cgx * 8u) * pitch_q + m0 / 2u + part * 16u;
         if (cgx * 8u < cols && part < n_rg) {
 #pragma unroll
@@ -346,14 +359,21 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         }
     }
     if (tid < cols) {
+        // the column scales of this k-row: NRG bytes, in the widest pieces the address allows
         uint8_t *dst = out_sf + (size_t)(k0 + tid) * pitch_sf + m0 / 32u;
-        const uint32_t *sp = reinterpret_cast<const uint32_t *>(&s_col_sf[tid * 8]);
-        if (n_rg == 8u && (reinterpret_cast<uintptr_t>(dst) & 3u) == 0u) {
-            reinterpret_cast<uint32_t *>(dst)[0] = sp[0];
-            reinterpret_cast<uint32_t *>(dst)[1] = sp[1];
+        const uint8_t *src = &s_col_sf[tid * NRG];
+        const uintptr_t al = reinterpret_cast<uintptr_t>(dst);
+        if (n_rg == (uint32_t)NRG && (al & (NRG - 1u)) == 0u) {
+            if (NRG == 16)
+                *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+            else
+                *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<const u32x2 *>(src);
+        } else if ((n_rg & 3u) == 0u && (al & 3u) == 0u) {
+            for (uint32_t g = 0; g < n_rg; g += 4)
+                *reinterpret_cast<uint32_t *>(dst + g) = *reinterpret_cast<const uint32_t *>(src + g);
         } else {
             for (uint32_t g = 0; g < n_rg; ++g)
-                dst[g] = s_col_sf[tid * 8 + g];
+                dst[g] = src[g];
         }
     }
 }
@@ -371,7 +391,7 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.num_experts = num_experts;
     a.M = (uint32_t)M;
     a.K = (uint32_t)K;
-    // upper bound on the number of 256-row tiles: every expert may end in a partial tile
+    // upper bound on the number of row tiles: every expert may end in a partial tile
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
