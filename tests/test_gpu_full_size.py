@@ -1,0 +1,130 @@
+"""GPU parity at the full sizes of the five configurations and of the benchmark workload,
+in the launch configuration bench.py times.  Outputs are compared with the CPU oracle bit
+for bit: completely where the oracle finishes in seconds (it runs over row ranges in a thread
+pool), on sampled rows plus structural properties for the 524288-row dispatch payload."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_02731_amd as mx
+from oracle import parallel as par
+from oracle import ref
+from paper_2603_02731_amd import synth
+from tests.test_gpu_parity import assert_same, host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def target():
+    """The benchmark workload: [65536, 7168] Student-t activations, generated on the GPU."""
+    x8, s = synth.student_t_fp8(65536, 7168, seed=0, device=DEV)
+    q, sf = mx.mxfp4_quant_from_fp8(x8, s)
+    torch.cuda.synchronize()
+    return {"x8": x8, "s": s, "q": q, "sf": sf}
+
+
+def test_config2_quant_dequant_4096x7168():
+    x8, s = synth.student_t_fp8(4096, 7168, seed=1, device=DEV)
+    q, sf = mx.mxfp4_quant_from_fp8(x8, s)
+    wq, wsf = par.quant(host(x8), host(s))
+    assert q.shape == (4096, 3584) and sf.shape == (4096, 224)
+    assert_same(host(sf), wsf, "cfg2 scale bytes")
+    assert_same(host(q), wq, "cfg2 nibbles")
+    x, xs = mx.mxfp4_dequant_to_fp8(q, sf)
+    wx, wxs = par.dequant(wq, wsf)
+    assert_same(host(xs), wxs, "cfg2 tile scales")
+    assert_same(host(x), wx, "cfg2 E4M3 bytes")
+
+
+def test_config3_row_to_col_16384x2048():
+    x8, s = synth.swiglu_fp8(16384, 2048, seed=2, device=DEV)
+    wq, wsf = par.quant(host(x8), host(s))            # the input of this config comes from the oracle
+    qc, sc = mx.mxfp4_row_to_col(torch.from_numpy(wq).to(DEV), torch.from_numpy(wsf).to(DEV))
+    wqc, wsc = par.row_to_col(wq, wsf)
+    assert qc.shape == (2048, 8192) and sc.shape == (2048, 512)
+    assert_same(host(sc), wsc, "cfg3 column scale bytes")
+    assert_same(host(qc), wqc, "cfg3 column nibbles")
+
+
+def test_config4_grouped_32_experts():
+    off, counts = synth.expert_offsets(seed=3, num_experts=32, total_tokens=65536, pad_to=128)
+    M = int(off[-1])
+    offd = off.to(DEV)
+    # quant path: FP8 [sum T_e, 7168], padding rows zero
+    x8, s = synth.student_t_fp8(M, 7168, seed=4, device=DEV)
+    x8, s = synth.zero_padding_rows(x8, s, off, counts)
+    q, sf = mx.mxfp4_quant_from_fp8_grouped(x8, s, offd)
+    wq, wsf = par.quant(host(x8), host(s))             # grouped == flat, pinned on the CPU
+    assert_same(host(sf), wsf, "cfg4 quant scale bytes")
+    assert_same(host(q), wq, "cfg4 quant nibbles")
+    del x8, s, q, sf, wq, wsf
+    # row->col path: MXFP4 [sum T_e, 2048]
+    y8, ys = synth.swiglu_fp8(M, 2048, seed=5, device=DEV)
+    y8, ys = synth.zero_padding_rows(y8, ys, off, counts)
+    rq, rsf = par.quant(host(y8), host(ys))
+    qc, sc = mx.mxfp4_row_to_col_grouped(torch.from_numpy(rq).to(DEV), torch.from_numpy(rsf).to(DEV), offd)
+    qc, sc = host(qc), host(sc)
+    K = 2048
+    for e in range(32):                                # per expert against the flat oracle routine
+        lo, hi = int(off[e]), int(off[e + 1])
+        wqc, wsc = par.row_to_col(rq[lo:hi], rsf[lo:hi], workers=4)
+        assert_same(sc[K * lo // 32: K * hi // 32].reshape(K, (hi - lo) // 32), wsc, f"cfg4 expert {e} scales")
+        assert_same(qc[K * lo // 2: K * hi // 2].reshape(K, (hi - lo) // 2), wqc, f"cfg4 expert {e} nibbles")
+
+
+def test_target_quant_65536x7168(target):
+    wq, wsf = par.quant(host(target["x8"]), host(target["s"]))
+    assert_same(host(target["sf"]), wsf, "target scale bytes")
+    assert_same(host(target["q"]), wq, "target nibbles")
+
+
+def test_target_dequant_65536x7168(target):
+    x, xs = mx.mxfp4_dequant_to_fp8(target["q"], target["sf"])
+    wx, wxs = par.dequant(host(target["q"]), host(target["sf"]))
+    assert_same(host(xs), wxs, "target tile scales")
+    assert_same(host(x), wx, "target E4M3 bytes")
+
+
+def test_target_row_to_col_65536x7168(target):
+    qc, sc = mx.mxfp4_row_to_col(target["q"], target["sf"])
+    wqc, wsc = par.row_to_col(host(target["q"]), host(target["sf"]))
+    assert_same(host(sc), wsc, "target column scale bytes")
+    assert_same(host(qc), wqc, "target column nibbles")
+
+
+def test_config5_dispatch_payload_round_trip(target):
+    x8, s = target["x8"], target["s"]
+    M, K, top_k = 65536, 7168, 8
+    idx = synth.routing_indices(seed=6, num_tokens=M, top_k=top_k, device=DEV)
+    Mo = M * top_k
+    rec = K // 2 + K // 32                                   # 3808-byte records: nibbles then scales
+    buf = torch.empty(Mo * rec, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec)
+    recs = buf.view(Mo, rec)
+    # property that holds at any size: every output row is the planar quantization of its source row
+    qsrc, sfsrc = target["q"], target["sf"]
+    li = idx.long()
+    for lo in range(0, Mo, 65536):
+        sl = slice(lo, lo + 65536)
+        assert torch.equal(recs[sl, : K // 2], qsrc[li[sl]])
+        assert torch.equal(recs[sl, K // 2:], sfsrc[li[sl]])
+    # sampled rows straight against the oracle (gathered form)
+    g = torch.Generator().manual_seed(7)
+    rows = torch.randperm(Mo, generator=g)[:4096].sort().values
+    xs_h, s_h = host(x8), host(s)
+    wq, wsf = ref.quant_from_fp8(xs_h, s_h, gather_idx=host(idx)[rows.numpy()])
+    got = host(recs[rows.to(DEV)])
+    assert_same(got[:, : K // 2], wq, "cfg5 sampled record nibbles")
+    assert_same(got[:, K // 2:], wsf, "cfg5 sampled record scales")
+    # and back: dequantize the whole payload from the records, check sampled rows
+    x = torch.empty((Mo, K), dtype=torch.uint8, device=DEV)
+    xsc = torch.empty((Mo, K // 128), dtype=torch.float32, device=DEV)
+    mx.mxfp4_dequant_to_fp8(buf, buf[K // 2:], M=Mo, K=K, ld_q=rec, ld_sf=rec, x=x, x_scale=xsc)
+    wx, wxs = par.dequant(wq, wsf)
+    assert_same(host(x[rows.to(DEV)]), wx, "cfg5 sampled dequantized bytes")
+    assert_same(host(xsc[rows.to(DEV)]), wxs, "cfg5 sampled tile scales")
+    # sizes: the closed-form payloads
+    assert buf.numel() == synth.payload_bytes(Mo, K)["mxfp4"]
+    assert x.numel() + 4 * xsc.numel() == synth.payload_bytes(Mo, K)["fp8"]
