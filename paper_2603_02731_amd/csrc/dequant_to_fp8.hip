@@ -23,7 +23,10 @@
 namespace mxfp4 {
 
 constexpr int DEQUANT_THREADS = 256;
-constexpr int DEQUANT_UNROLL = 2;
+#ifndef MXFP4_DEQUANT_UNROLL
+#define MXFP4_DEQUANT_UNROLL 2
+#endif
+constexpr int DEQUANT_UNROLL = MXFP4_DEQUANT_UNROLL;
 
 // E4M3 magnitude byte of e2m1(code) * 2^(6-d) for d in [12, 19], rounded to nearest-even.
 // e2m1(code) = h/2 with h below; in units of the E4M3 subnormal quantum 2^-9 the value is

@@ -18,7 +18,10 @@
 namespace mxfp4 {
 
 constexpr int QUANT_THREADS = 256;
-constexpr int QUANT_UNROLL = 2;
+#ifndef MXFP4_QUANT_UNROLL
+#define MXFP4_QUANT_UNROLL 2
+#endif
+constexpr int QUANT_UNROLL = MXFP4_QUANT_UNROLL;
 
 struct QuantArgs {
     const uint8_t *x;
