@@ -179,6 +179,55 @@ int mxfp4_ref_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_s
     return 0;
 }
 
+/* ---------------------------------------------------------------- BF16 -> MXFP4 */
+
+/* Value of a BF16 bit pattern (the upper half of an FP32); NaN and +-inf as such. */
+static double bf16_value(unsigned h)
+{
+    unsigned sign = h >> 15, e = (h >> 7) & 0xFFu, m = h & 0x7Fu;
+    double a;
+    if (e == 0xFFu)
+        a = m ? NAN : INFINITY;
+    else if (e == 0)
+        a = ldexp((double)m, -133); /* subnormal: (m/128) * 2^-126 */
+    else
+        a = ldexp(1.0 + (double)m / 128.0, (int)e - 127);
+    return sign ? -a : a;
+}
+
+/* The row-wise quantizer as the paper states it (section 3.1, BF16 input): BF16 [M,K] ->
+ * packed E2M1 [M,K/2] (row stride ld_q) + UE8M0 [M,K/32] (row stride ld_sf).  The element
+ * values are the BF16 values themselves.  K % 128 == 0 like everywhere in this library. */
+int mxfp4_ref_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *q, int64_t ld_q, uint8_t *sf,
+                              int64_t ld_sf)
+{
+    if (M < 0 || K < 0 || K % 128 != 0)
+        return -1;
+    if (M == 0 || K == 0)
+        return 0;
+    if (!x || !q || !sf || ld_q < K / 2 || ld_sf < K / 32)
+        return -1;
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < K / 32; ++j) {
+            double v[32];
+            int has_nan = 0;
+            for (int e = 0; e < 32; ++e) {
+                v[e] = bf16_value(x[i * K + j * 32 + e]);
+                if (isnan(v[e])) {
+                    has_nan = 1;
+                    v[e] = 0.0;
+                }
+            }
+            unsigned char code[32];
+            unsigned b = quantize_block32(v, has_nan, code);
+            sf[i * ld_sf + j] = (uint8_t)b;
+            for (int e = 0; e < 16; ++e)
+                q[i * ld_q + j * 16 + e] = (uint8_t)(code[2 * e] | (code[2 * e + 1] << 4));
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- MXFP4 -> FP8 */
 
 /* Packed E2M1 [M,K/2] + UE8M0 [M,K/32]  ->  E4M3 [M,K] + FP32 scale per 1x128 tile

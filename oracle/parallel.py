@@ -23,6 +23,14 @@ def quant(x, s, workers=WORKERS):
     return np.concatenate([o[0] for o in outs]), np.concatenate([o[1] for o in outs])
 
 
+def quant_bf16(x, workers=WORKERS):
+    x = np.ascontiguousarray(x)
+    rs = _ranges(x.shape[0], 1, workers)
+    with ThreadPoolExecutor(workers) as ex:
+        outs = list(ex.map(lambda r: ref.quant_from_bf16(x[r[0]:r[1]]), rs))
+    return np.concatenate([o[0] for o in outs]), np.concatenate([o[1] for o in outs])
+
+
 def dequant(q, sf, workers=WORKERS):
     q, sf = np.ascontiguousarray(q), np.ascontiguousarray(sf)
     rs = _ranges(q.shape[0], 1, workers)

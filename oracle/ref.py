@@ -27,6 +27,8 @@ def lib():
             _build.build(force=True)
         L = ctypes.CDLL(path)
         L.mxfp4_ref_quant_from_fp8.argtypes = [_u8p, _f32p, _i64, _i64, _i32p, _i64, _u8p, _i64, _u8p, _i64]
+        L.mxfp4_ref_quant_from_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint16), _i64, _i64, _u8p, _i64, _u8p, _i64]
+        L.mxfp4_ref_quant_from_bf16.restype = ctypes.c_int
         L.mxfp4_ref_dequant_to_fp8.argtypes = [_u8p, _i64, _u8p, _i64, _i64, _i64, _u8p, _f32p]
         L.mxfp4_ref_row_to_col.argtypes = [_u8p, _u8p, _i64, _i64, _u8p, _u8p]
         L.mxfp4_ref_quant_from_fp8_grouped.argtypes = [_u8p, _f32p, _i32p, ctypes.c_int32, _i64, _i64, _u8p, _u8p]
@@ -77,6 +79,18 @@ def quant_from_fp8(x, x_scale, gather_idx=None):
     rc = lib().mxfp4_ref_quant_from_fp8(_p(x, _u8p), _p(x_scale, _f32p), M, K, gp, Mo,
                                         _p(q, _u8p), K // 2, _p(sf, _u8p), K // 32)
     _check(rc, "quant_from_fp8")
+    return q, sf
+
+
+def quant_from_bf16(x):
+    """x uint16 [M,K] (BF16 bit patterns) -> (q [M,K/2], sf [M,K/32])."""
+    x = _c(x, np.uint16)
+    M, K = x.shape
+    q = np.empty((M, K // 2), np.uint8)
+    sf = np.empty((M, K // 32), np.uint8)
+    rc = lib().mxfp4_ref_quant_from_bf16(_p(x, ctypes.POINTER(ctypes.c_uint16)), M, K,
+                                         _p(q, _u8p), K // 2, _p(sf, _u8p), K // 32)
+    _check(rc, "quant_from_bf16")
     return q, sf
 
 

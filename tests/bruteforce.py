@@ -138,3 +138,20 @@ def row_to_col_tile(nib, sf_rows):
         sc.append(b)
         codes.append(c)
     return sc, codes
+
+
+def bf16_fraction(h):
+    """BF16 bit pattern (sign stripped by the caller or not) -> (sign, magnitude as Fraction or INF); NaN -> None."""
+    sign, e, m = (h >> 15) & 1, (h >> 7) & 0xFF, h & 0x7F
+    if e == 0xFF:
+        return None if m else (sign, INF)
+    if e == 0:
+        return sign, Fraction(m, 128) * pow2(-126)
+    return sign, (1 + Fraction(m, 128)) * pow2(e - 127)
+
+
+def quant_block_from_bf16(halves32):
+    vals = [bf16_fraction(h) for h in halves32]
+    if any(v is None for v in vals):
+        return 0xFF, [0] * 32
+    return quant_block(vals)
