@@ -190,6 +190,18 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
+    # the paper's BF16-source row quantizer on the same activations (2 B read + 0.53125 B written per element)
+    xbf = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    for r0 in range(0, M, 8192):
+        xbf[r0:r0 + 8192] = (x8[r0:r0 + 8192].view(torch.float8_e4m3fn).float()
+                             * s[r0:r0 + 8192].repeat_interleave(128, dim=1)).to(torch.bfloat16)
+    qb = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+    sb = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
+    us = timed(lambda: mx.mxfp4_quant_from_bf16(xbf, q=qb, sf=sb))
+    b = M * K * (2.0 + 0.53125)
+    res["quant_from_bf16"] = {"us": us, "GB/s": b / us * 1e-3, "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
+    del xbf, qb, sb
+
     top_k = 8
     idx = synth.routing_indices(seed=a.seed, num_tokens=M, top_k=top_k, device=dev)
     Mo = idx.shape[0]

@@ -72,6 +72,15 @@ mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_
                                   const int32_t *gather_idx, int64_t M_out, uint8_t *q,
                                   int64_t ld_q, uint8_t *sf, int64_t ld_sf, void *hip_stream);
 
+/* BF16 -> MXFP4: the row-wise quantizer as the paper states it (sec. 3.1, BF16ToFP4Row): the same
+ * scale rule and rounding, applied to the BF16 values themselves.  NaN -> block scale 0xFF, codes 0;
+ * +-inf -> block scale 254, code 7.
+ *   x   BF16 bit patterns [M, K] dense, 16-byte aligned
+ *   q   packed E2M1, row stride ld_q bytes (>= K/2); pointer and stride 4-byte aligned
+ *   sf  UE8M0, row stride ld_sf bytes (>= K/32); pointer and stride 4-byte aligned */
+mxfp4_status mxfp4_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *q, int64_t ld_q,
+                                   uint8_t *sf, int64_t ld_sf, void *hip_stream);
+
 /* MXFP4 -> FP8 (paper sec. 3.3, Algorithm 1: direct bit-wise remap with hierarchical scale
  * alignment).  Per 128-element tile with scale bytes b0..b3: the FP32 tile scale is
  * 2^(max(b) - 6 - 127), and every element becomes the E4M3 code of

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libmxfp4.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_OFFSETS, ERR_LAUNCH = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
+EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
            "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_status_string")
 
 _lib = None
@@ -36,6 +36,7 @@ def lib():
             _build.build(force=True)
         L = ctypes.CDLL(LIB_PATH)  # raises OSError if it cannot be loaded: no fallback
         L.mxfp4_quant_from_fp8.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp]
+        L.mxfp4_quant_from_bf16.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.mxfp4_dequant_to_fp8.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_row_to_col.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_quant_from_fp8_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
@@ -94,6 +95,21 @@ def mxfp4_quant_from_fp8(x, x_scale, gather_idx=None, q=None, sf=None, ld_q=None
                                     None if gather_idx is None else gather_idx.data_ptr(), M_out,
                                     q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream))
     _check("mxfp4_quant_from_fp8", st)
+    return q, sf
+
+
+def mxfp4_quant_from_bf16(x, q=None, sf=None, ld_q=None, ld_sf=None, stream=None):
+    """x bfloat16 [M,K] -> (q uint8 [M,K/2], sf uint8 [M,K/32])."""
+    _dev(x, torch.bfloat16, "x")
+    M, K = x.shape
+    if q is None:
+        q = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    if sf is None:
+        sf = torch.empty((M, K // 32), dtype=torch.uint8, device=x.device)
+    ld_q = K // 2 if ld_q is None else ld_q
+    ld_sf = K // 32 if ld_sf is None else ld_sf
+    st = lib().mxfp4_quant_from_bf16(x.data_ptr(), M, K, q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream))
+    _check("mxfp4_quant_from_bf16", st)
     return q, sf
 
 

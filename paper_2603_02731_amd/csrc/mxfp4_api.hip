@@ -40,6 +40,22 @@ mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_
                                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+mxfp4_status mxfp4_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *q, int64_t ld_q, uint8_t *sf,
+                                   int64_t ld_sf, void *hip_stream)
+{
+    if (M < 0 || K < 0 || K % 128 != 0)
+        return MXFP4_ERR_SHAPE;
+    if (M == 0 || K == 0)
+        return MXFP4_OK;
+    if (!x || !q || !sf)
+        return MXFP4_ERR_NULL;
+    if (ld_q < K / 2 || ld_sf < K / 32 || M >= kMaxRows || K >= kMaxRows || M * (K / 8) >= kMaxWorkItems)
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(q, 4) || ld_q % 4 != 0 || !aligned(sf, 4) || ld_sf % 4 != 0)
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_quant_from_bf16(x, M, K, q, ld_q, sf, ld_sf, static_cast<hipStream_t>(hip_stream)));
+}
+
 mxfp4_status mxfp4_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, int64_t ld_sf, int64_t M,
                                   int64_t K, uint8_t *x, float *x_scale, void *hip_stream)
 {

@@ -49,6 +49,12 @@ __device__ __forceinline__ uint32_t row_shift_left4(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104 /* row_shl:4 */, 0xF, 0xF, true);
 }
 
+// Value of lane i+8 of the same row of 16 lanes (0 where there is none), by DPP.
+__device__ __forceinline__ uint32_t row_shift_left8(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x108 /* row_shl:8 */, 0xF, 0xF, true);
+}
+
 // NaN-propagating maximum of |a|, |b| and c.
 __device__ __forceinline__ float max3_abs_nan(float a, float b, float c)
 {

@@ -246,3 +246,47 @@ def test_empty_and_argument_errors():
     with pytest.raises(mx.Mxfp4Error) as e:
         mx.mxfp4_row_to_col(q[:16], sf[:16])                            # M % 32 != 0
     assert e.value.status == -2
+
+
+# ------------------------------------------------------------------ BF16 -> MXFP4 (the paper's row-wise kernel)
+
+def check_quant_bf16(bits):
+    x = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(DEV)
+    q, sf = mx.mxfp4_quant_from_bf16(x)
+    wq, wsf = par.quant_bf16(bits)
+    assert_same(host(sf), wsf, "bf16 quant scale bytes")
+    assert_same(host(q), wq, "bf16 quant nibbles")
+
+
+def test_quant_bf16_every_bit_pattern():
+    # all 65536 patterns (every exponent, subnormals, inf, NaN), shuffled over blocks, several seeds;
+    # then each exponent's patterns together so that small values are not always flushed by a big neighbour
+    rng = np.random.default_rng(0)
+    rows = [rng.permutation(65536).astype(np.uint16).reshape(64, 1024) for _ in range(3)]
+    by_exp = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(2, 256, 128)   # [sign][exp][mant]
+    grouped = np.concatenate([by_exp[0], by_exp[1]], axis=1)                            # one exponent per row
+    rows.append(np.tile(grouped, (1, 4))[:, :1024])
+    mixed = grouped.copy()
+    for r in range(256):
+        rng.shuffle(mixed[r])
+    rows.append(np.tile(mixed, (1, 4))[:, :1024])
+    check_quant_bf16(np.concatenate(rows))
+
+
+def test_quant_bf16_activations_and_strides():
+    g = torch.Generator().manual_seed(3)
+    v = torch.randn(200, 1152, generator=g) * torch.logspace(-3, 3, 1152)
+    v[5, 40:72] = 0
+    v[6, 100] = float("inf")
+    v[7, 300] = float("nan")
+    xb = v.to(torch.bfloat16)
+    bits = xb.view(torch.uint16).numpy()
+    check_quant_bf16(bits)
+    K = 1152
+    rec = K // 2 + K // 32
+    buf = torch.zeros(200 * rec, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_bf16(xb.to(DEV), q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec)
+    wq, wsf = ref.quant_from_bf16(bits)
+    recs = host(buf).reshape(200, rec)
+    assert_same(recs[:, : K // 2], wq, "bf16 record nibbles")
+    assert_same(recs[:, K // 2:], wsf, "bf16 record scales")
