@@ -27,7 +27,7 @@ def parse():
     p.add_argument("--rows", type=int, default=65536, help="M of the workload (tokens)")
     p.add_argument("--hidden", type=int, default=7168, help="K of the workload")
     p.add_argument("--seed", type=int, default=0)
-    p.add_argument("--cpu-sample-rows", type=int, default=32768)
+    p.add_argument("--cpu-sample-rows", type=int, default=65536)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--copy-calibration", action="store_true",
                    help="run only plain device copies of a known size (512 MiB read + 512 MiB written per "
