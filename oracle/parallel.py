@@ -45,3 +45,11 @@ def row_to_col(q, sf, workers=WORKERS):
     with ThreadPoolExecutor(workers) as ex:
         outs = list(ex.map(lambda r: ref.row_to_col(q[r[0]:r[1]], sf[r[0]:r[1]]), rs))
     return np.concatenate([o[0] for o in outs], axis=1), np.concatenate([o[1] for o in outs], axis=1)
+
+
+def row_to_fp8_col(q, sf, workers=WORKERS):
+    q, sf = np.ascontiguousarray(q), np.ascontiguousarray(sf)
+    rs = _ranges(q.shape[0], 128, workers)
+    with ThreadPoolExecutor(workers) as ex:
+        outs = list(ex.map(lambda r: ref.row_to_fp8_col(q[r[0]:r[1]], sf[r[0]:r[1]]), rs))
+    return np.concatenate([o[0] for o in outs], axis=1), np.concatenate([o[1] for o in outs], axis=1)

@@ -33,6 +33,10 @@ def lib():
         L.mxfp4_ref_row_to_col.argtypes = [_u8p, _u8p, _i64, _i64, _u8p, _u8p]
         L.mxfp4_ref_quant_from_fp8_grouped.argtypes = [_u8p, _f32p, _i32p, ctypes.c_int32, _i64, _i64, _u8p, _u8p]
         L.mxfp4_ref_row_to_col_grouped.argtypes = [_u8p, _u8p, _i32p, ctypes.c_int32, _i64, _i64, _u8p, _u8p]
+        L.mxfp4_ref_row_to_fp8_col.argtypes = [_u8p, _u8p, _i64, _i64, _u8p, _f32p]
+        L.mxfp4_ref_row_to_fp8_col_grouped.argtypes = [_u8p, _u8p, _i32p, ctypes.c_int32, _i64, _i64, _u8p, _f32p]
+        L.mxfp4_ref_row_to_fp8_col.restype = ctypes.c_int
+        L.mxfp4_ref_row_to_fp8_col_grouped.restype = ctypes.c_int
         for f in (L.mxfp4_ref_quant_from_fp8, L.mxfp4_ref_dequant_to_fp8, L.mxfp4_ref_row_to_col,
                   L.mxfp4_ref_quant_from_fp8_grouped, L.mxfp4_ref_row_to_col_grouped):
             f.restype = ctypes.c_int
@@ -117,6 +121,32 @@ def row_to_col(q_row, sf_row):
     rc = lib().mxfp4_ref_row_to_col(_p(q_row, _u8p), _p(sf_row, _u8p), M, K, _p(qc, _u8p), _p(sc, _u8p))
     _check(rc, "row_to_col")
     return qc, sc
+
+
+def row_to_fp8_col(q_row, sf_row):
+    """[M,K/2] + [M,K/32] -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128])."""
+    q_row = _c(q_row, np.uint8)
+    sf_row = _c(sf_row, np.uint8)
+    M, K = q_row.shape[0], q_row.shape[1] * 2
+    xc = np.empty((K, M), np.uint8)
+    xs = np.empty((K, M // 128), np.float32)
+    rc = lib().mxfp4_ref_row_to_fp8_col(_p(q_row, _u8p), _p(sf_row, _u8p), M, K, _p(xc, _u8p), _p(xs, _f32p))
+    _check(rc, "row_to_fp8_col")
+    return xc, xs
+
+
+def row_to_fp8_col_grouped(q_row, sf_row, expert_offsets):
+    """Flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,T_e/128] at K*off_e/128."""
+    q_row = _c(q_row, np.uint8)
+    sf_row = _c(sf_row, np.uint8)
+    off = _c(expert_offsets, np.int32)
+    M, K = q_row.shape[0], q_row.shape[1] * 2
+    xc = np.empty(M * K, np.uint8)
+    xs = np.empty(M * K // 128, np.float32)
+    rc = lib().mxfp4_ref_row_to_fp8_col_grouped(_p(q_row, _u8p), _p(sf_row, _u8p), _p(off, _i32p),
+                                                off.shape[0] - 1, M, K, _p(xc, _u8p), _p(xs, _f32p))
+    _check(rc, "row_to_fp8_col_grouped")
+    return xc, xs
 
 
 def quant_from_fp8_grouped(x, x_scale, expert_offsets):

@@ -155,3 +155,17 @@ def quant_block_from_bf16(halves32):
     if any(v is None for v in vals):
         return 0xFF, [0] * 32
     return quant_block(vals)
+
+
+def row_to_fp8_col_column(nibs, sf_bytes):
+    """One output column group: nibs[m], sf_bytes[m] for 128 consecutive rows m at one k (no NaN byte).
+    The group's scale is the smallest power of two S = 2^(max b - 6 - 127) that keeps the largest
+    representable element, 6 * 2^(max b - 127), at 6 * 2^6 = 384 <= 448; each element is its real
+    value divided by S, to the nearest E4M3 (ties to the even code).  Returns (S, [128 bytes])."""
+    bmax = max(sf_bytes)
+    S = pow2(bmax - 6 - 127)
+    out = []
+    for n, b in zip(nibs, sf_bytes):
+        real = E2M1_GRID[n & 7] * pow2(b - 127)
+        out.append(((n >> 3) << 7) | nearest_even_code(real / S, E4M3_GRID))
+    return S, out
