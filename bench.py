@@ -174,7 +174,8 @@ def main():
 
 
 def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
-    """Gathered quant (top-8 dispatch emulation), per-token records, grouped row->col."""
+    """BF16-source quant, gathered quant (top-8 dispatch emulation), per-token records, FP8 column output,
+    grouped forms."""
     dev = x8.device
     M, K = x8.shape
     res = {}
@@ -218,10 +219,24 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
     us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec))
     res["quant_gather_top8_records"] = {"us": us, "compulsory_GB/s": compulsory / us * 1e-3}
     del qg, sg, buf
+    # the paper's literal weight-gradient kernel: row-blocked MXFP4 -> column-wise FP8
+    # (0.53125 B read + 1.03125 B written per element)
+    xc = torch.empty((K, M), dtype=torch.uint8, device=dev)
+    xcs = torch.empty((K, M // 128), dtype=torch.float32, device=dev)
+    us = timed(lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs))
+    b = M * K * (0.53125 + 1.03125)
+    res["row_to_fp8_col"] = {"us": us, "GB/s": b / us * 1e-3, "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
     off, _ = synth.expert_offsets(seed=a.seed, num_experts=32, total_tokens=M - 32 * 128, pad_to=128)
     Mt = int(off[-1])
     if Mt <= M:
         offd = off.to(dev)
+        us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mt], sf[:Mt], offd, x_col=xc.view(-1)[:Mt * K],
+                                                           x_col_scale=xcs.view(-1)[:Mt * K // 128]))
+        b = Mt * K * (0.53125 + 1.03125)
+        res["row_to_fp8_col_grouped_32_experts"] = {"rows": Mt, "us": us, "GB/s": b / us * 1e-3,
+                                                    "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
+    del xc, xcs
+    if Mt <= M:
         qc = torch.empty(Mt * K // 2, dtype=torch.uint8, device=dev)
         scc = torch.empty(Mt * K // 32, dtype=torch.uint8, device=dev)
         us = timed(lambda: mx.mxfp4_row_to_col_grouped(q[:Mt], sf[:Mt], offd, q_col=qc, sf_col=scc))

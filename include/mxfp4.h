@@ -44,8 +44,8 @@ typedef int mxfp4_status;
 enum {
     MXFP4_OK = 0,
     MXFP4_ERR_NULL = -1,    /* a required pointer is NULL */
-    MXFP4_ERR_SHAPE = -2,   /* negative size, K % 128 != 0, M % 32 != 0 where column blocks are
-                               formed, a row stride smaller than the row, or a size beyond
+    MXFP4_ERR_SHAPE = -2,   /* negative size, K % 128 != 0, M % 32 != 0 (M % 128 != 0 for FP8
+                               output) where column blocks are formed, a row stride smaller than the row, or a size beyond
                                what the 32-bit work indices of a kernel can address */
     MXFP4_ERR_ALIGN = -3,   /* pointer or row stride not aligned as stated per entry point */
     MXFP4_ERR_OFFSETS = -4, /* grouped: num_experts <= 0 or beyond MXFP4_MAX_EXPERTS */
@@ -122,6 +122,29 @@ mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_ro
                                       const int32_t *expert_offsets, int32_t num_experts,
                                       int64_t M_total, int64_t K, uint8_t *q_col, uint8_t *sf_col,
                                       void *hip_stream);
+
+/* Row-blocked MXFP4 -> the transposed matrix in FP8 for the weight-gradient GEMM (paper sec. 3.4,
+ * the fused de-quantize / transpose / re-quantize kernel with FP8 output; the FP4 -> FP8 step is
+ * the hierarchical scale alignment of sec. 3.3, Algorithm 1, taken along m).  For output row k and
+ * each group of 128 consecutive rows m, with b_m = sf_row[m][k/32]:
+ *   x_col_scale[k][m/128] = 2^(max(b) - 6 - 127)   (an FP32 subnormal when max(b) < 7)
+ *   x_col[k][m]           = E4M3 code of e2m1(code[m][k]) * 2^(6 - (max(b) - b_m)),
+ * rounded to nearest-even through the E4M3 subnormals; lossless while max(b) - b_m <= 14.
+ * A 0xFF scale byte makes its group's scale NaN for the 32 k of its block and its own elements
+ * 0x7F; the other rows align to the maximum of the non-NaN bytes.
+ *   q_row [M, K/2] dense, 4-byte aligned;  sf_row [M, K/32] dense, 4-byte aligned
+ *   x_col E4M3 [K, M] dense, 16-byte aligned;  x_col_scale FP32 [K, M/128] dense, 4-byte aligned
+ *   M % 128 == 0. */
+mxfp4_status mxfp4_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                                  uint8_t *x_col, float *x_col_scale, void *hip_stream);
+
+/* The same per expert (expert_offsets as above, every T_e a multiple of 128): expert e's output is
+ * its own dense [K, T_e] and [K, T_e/128] matrices at element offsets K*off_e of x_col and
+ * K*off_e/128 of x_col_scale.  No scale group crosses an expert boundary. */
+mxfp4_status mxfp4_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                          const int32_t *expert_offsets, int32_t num_experts,
+                                          int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale,
+                                          void *hip_stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp4_status_string(mxfp4_status status);

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libmxfp4.so")
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_OFFSETS, ERR_LAUNCH = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
-           "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_status_string")
+           "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_row_to_fp8_col",
+           "mxfp4_row_to_fp8_col_grouped", "mxfp4_status_string")
 
 _lib = None
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -41,6 +42,8 @@ def lib():
         L.mxfp4_row_to_col.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_quant_from_fp8_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_row_to_col_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
+        L.mxfp4_row_to_fp8_col.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp]
+        L.mxfp4_row_to_fp8_col_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
         for n in EXPORTS[:-1]:
             getattr(L, n).restype = ctypes.c_int
         L.mxfp4_status_string.argtypes = [ctypes.c_int]
@@ -175,3 +178,35 @@ def mxfp4_row_to_col_grouped(q_row, sf_row, expert_offsets, q_col=None, sf_col=N
                                         _stream(stream))
     _check("mxfp4_row_to_col_grouped", st)
     return q_col, sf_col
+
+
+def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=None):
+    """[M,K/2] + [M,K/32] row-blocked MXFP4 -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128])."""
+    _dev(q_row, torch.uint8, "q_row")
+    _dev(sf_row, torch.uint8, "sf_row")
+    M, K = q_row.shape[0], q_row.shape[1] * 2
+    if x_col is None:
+        x_col = torch.empty((K, M), dtype=torch.uint8, device=q_row.device)
+    if x_col_scale is None:
+        x_col_scale = torch.empty((K, M // 128), dtype=torch.float32, device=q_row.device)
+    st = lib().mxfp4_row_to_fp8_col(q_row.data_ptr(), sf_row.data_ptr(), M, K, x_col.data_ptr(),
+                                    x_col_scale.data_ptr(), _stream(stream))
+    _check("mxfp4_row_to_fp8_col", st)
+    return x_col, x_col_scale
+
+
+def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_col_scale=None, stream=None):
+    """Outputs are flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,T_e/128] at K*off_e/128."""
+    _dev(q_row, torch.uint8, "q_row")
+    _dev(sf_row, torch.uint8, "sf_row")
+    _dev(expert_offsets, torch.int32, "expert_offsets")
+    M, K = q_row.shape[0], q_row.shape[1] * 2
+    if x_col is None:
+        x_col = torch.empty(M * K, dtype=torch.uint8, device=q_row.device)
+    if x_col_scale is None:
+        x_col_scale = torch.empty(M * K // 128, dtype=torch.float32, device=q_row.device)
+    st = lib().mxfp4_row_to_fp8_col_grouped(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(),
+                                            expert_offsets.shape[0] - 1, M, K, x_col.data_ptr(),
+                                            x_col_scale.data_ptr(), _stream(stream))
+    _check("mxfp4_row_to_fp8_col_grouped", st)
+    return x_col, x_col_scale

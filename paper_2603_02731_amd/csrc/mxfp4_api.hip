@@ -123,6 +123,45 @@ mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_ro
     return row_to_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, q_col, sf_col, hip_stream);
 }
 
+static mxfp4_status row_to_fp8_col_common(const uint8_t *q_row, const uint8_t *sf_row,
+                                          const int32_t *expert_offsets, int32_t num_experts, int64_t M,
+                                          int64_t K, uint8_t *x_col, float *x_col_scale, void *hip_stream)
+{
+    if (M < 0 || K < 0 || K % 128 != 0 || M % 128 != 0)
+        return MXFP4_ERR_SHAPE;
+    if (M == 0 || K == 0)
+        return MXFP4_OK;
+    if (!q_row || !sf_row || !x_col || !x_col_scale)
+        return MXFP4_ERR_NULL;
+    // byte offsets inside a 256-row tile are 32-bit, and so is the tile count
+    if (M >= kMaxRows || K > ((int64_t)1 << 24) ||
+        ((M + 255) / 256 + num_experts) * ((K + 255) / 256) >= ((int64_t)1 << 31))
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(q_row, 4) || !aligned(sf_row, 4) || !aligned(x_col, 16) || !aligned(x_col_scale, 4) ||
+        (expert_offsets && !aligned(expert_offsets, 4)))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_row_to_fp8_col(q_row, sf_row, expert_offsets, num_experts, M, K, x_col,
+                                                 x_col_scale, static_cast<hipStream_t>(hip_stream)));
+}
+
+mxfp4_status mxfp4_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                                  uint8_t *x_col, float *x_col_scale, void *hip_stream)
+{
+    return row_to_fp8_col_common(q_row, sf_row, nullptr, 0, M, K, x_col, x_col_scale, hip_stream);
+}
+
+mxfp4_status mxfp4_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                          const int32_t *expert_offsets, int32_t num_experts, int64_t M_total,
+                                          int64_t K, uint8_t *x_col, float *x_col_scale, void *hip_stream)
+{
+    if (num_experts <= 0 || num_experts > MXFP4_MAX_EXPERTS)
+        return MXFP4_ERR_OFFSETS;
+    if (!expert_offsets)
+        return MXFP4_ERR_NULL;
+    return row_to_fp8_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
+                                 hip_stream);
+}
+
 const char *mxfp4_status_string(mxfp4_status status)
 {
     switch (status) {

@@ -8,6 +8,8 @@
 //    honours FP32 subnormal sources.
 //  * v_cvt_scalef32_pk_f32_fp4 returns e2m1 * 2^(E-127) exactly, as FP32 subnormals where
 //    needed.
+//  * v_cvt_scalef32_pk_fp8_f32 computes RTNE(src / 2^(E-127)) onto OCP E4M3 with gradual
+//    underflow, keeps the sign of zero results, and puts its first source in the low byte.
 //  * v_maximum3_f32 propagates NaN.
 #pragma once
 
@@ -42,6 +44,7 @@ __device__ __forceinline__ uint32_t dpp_read(uint32_t v)
 constexpr int DPP_QUAD_XOR1 = 0xB1; // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_XOR2 = 0x4E; // quad_perm [2,3,0,1]
 constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> lane 7-i inside each group of 8
+constexpr int DPP_ROW_MIRROR = 0x140;      // lane i <-> lane 15-i inside each row of 16
 
 // Value of lane i+4 of the same row of 16 lanes (0 where there is none), by DPP.
 __device__ __forceinline__ uint32_t row_shift_left4(uint32_t v)
@@ -77,6 +80,34 @@ __device__ __forceinline__ uint32_t ue8m0_of_block_max(uint32_t gmax_bits)
     b = gmax_bits == 0x7F800000u ? 254 : b;
     b = gmax_bits > 0x7F800000u ? 255 : b;
     return (uint32_t)b;
+}
+
+// Workgroup -> tile for the transposing kernels.  The hardware deals consecutive workgroup ids
+// round-robin to the 8 XCDs, each with its own L2.  Id i therefore takes entry i/8 of XCD (i%8)'s
+// own contiguous share of a tile order in which MBM x MBK tiles form a macro block walked
+// m-fastest: the tiles an XCD has in flight together are neighbours along m (their output pieces
+// and their few-byte scale pieces complete whole lines in that L2) and along k (they share the
+// 32-byte sectors of the row scales).  Returns false for the ids that round the grid up.
+constexpr uint32_t NUM_XCD = 8;
+template <uint32_t MBM, uint32_t MBK>
+__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
+                                                  uint32_t *tile_m, uint32_t *tile_k)
+{
+    const uint32_t total = tiles_m * tiles_k;
+    const uint32_t per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
+    const uint32_t l = (id % NUM_XCD) * per_xcd + id / NUM_XCD;
+    if (id / NUM_XCD >= per_xcd || l >= total)
+        return false;
+    const uint32_t per_macro_row = MBM * tiles_k;
+    const uint32_t mg = l / per_macro_row;
+    const uint32_t rem = l - mg * per_macro_row;
+    const uint32_t mb_rows = min(MBM, tiles_m - mg * MBM);
+    const uint32_t kg = rem / (MBK * mb_rows);
+    const uint32_t rem2 = rem - kg * MBK * mb_rows;
+    const uint32_t k_in = rem2 / mb_rows;
+    *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
+    *tile_k = kg * MBK + k_in;
+    return true;
 }
 
 // Compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>).

@@ -22,4 +22,9 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
                              int32_t num_experts, int64_t M, int64_t K, uint8_t *q_col, uint8_t *sf_col,
                              hipStream_t stream);
 
+// expert_offsets == nullptr: the flat conversion of an [M, K] matrix.
+hipError_t launch_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                                 int32_t num_experts, int64_t M, int64_t K, uint8_t *x_col, float *x_col_scale,
+                                 hipStream_t stream);
+
 } // namespace mxfp4

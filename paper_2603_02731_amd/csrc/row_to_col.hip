@@ -63,32 +63,7 @@ struct RowToColArgs {
     uint32_t tiles_k; // 256-column tiles
 };
 
-// Workgroup -> tile.  The hardware deals consecutive workgroup ids round-robin to the 8 XCDs,
-// each with its own L2.  Id i therefore takes entry i/8 of XCD (i%8)'s own contiguous share
-// of a tile order in which MBM x MBK tiles form a macro block walked m-fastest: the tiles an
-// XCD has in flight together are neighbours along m (their 128-byte output pieces and 8-byte
-// column-scale pieces complete whole lines in that L2) and along k (they share the 32-byte
-// sectors of the row scales).
-constexpr uint32_t NUM_XCD = 8, MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK;
-__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
-                                                  uint32_t *tile_m, uint32_t *tile_k)
-{
-    const uint32_t total = tiles_m * tiles_k;
-    const uint32_t per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
-    const uint32_t l = (id % NUM_XCD) * per_xcd + id / NUM_XCD;
-    if (id / NUM_XCD >= per_xcd || l >= total)
-        return false;
-    const uint32_t per_macro_row = MBM * tiles_k;
-    const uint32_t mg = l / per_macro_row;
-    const uint32_t rem = l - mg * per_macro_row;
-    const uint32_t mb_rows = min(MBM, tiles_m - mg * MBM);
-    const uint32_t kg = rem / (MBK * mb_rows);
-    const uint32_t rem2 = rem - kg * MBK * mb_rows;
-    const uint32_t k_in = rem2 / mb_rows;
-    *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
-    *tile_k = kg * MBK + k_in;
-    return true;
-}
+constexpr uint32_t MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK; // macro block of the tile order
 
 // Scale operand of row I of a slice: its UE8M0 byte (byte I%4 of dword I/4) moved into bits
 // 30:23 with one shift.  What lands in the sign and mantissa bits belongs to the neighbouring
@@ -228,7 +203,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     uint8_t *s_col_sf = reinterpret_cast<uint8_t *>(s_out); // [k][PM*NRG], after the last tile is out
 
     uint32_t strip, tile_k;
-    if (!tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k))
+    if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k))
         return;
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)

@@ -41,16 +41,22 @@ def test_argument_validation_without_a_gpu():
     assert L.mxfp4_quant_from_fp8(a16, a16, -1, 128, None, -1, a16, 64, a16, 4, None) == binding.ERR_SHAPE
     assert L.mxfp4_dequant_to_fp8(a16, 64, a16, 4, 4, 130, a16, a16, None) == binding.ERR_SHAPE
     assert L.mxfp4_row_to_col(a16, a16, 48, 128, a16, a16, None) == binding.ERR_SHAPE
+    assert L.mxfp4_row_to_fp8_col(a16, a16, 96, 128, a16, a16, None) == binding.ERR_SHAPE
+    assert L.mxfp4_row_to_fp8_col(a16, a16, 128, 1 << 25, a16, a16, None) == binding.ERR_SHAPE
     # null pointers
     assert L.mxfp4_quant_from_fp8(None, a16, 4, 128, None, 4, a16, 64, a16, 4, None) == binding.ERR_NULL
     assert L.mxfp4_dequant_to_fp8(a16, 64, None, 4, 4, 128, a16, a16, None) == binding.ERR_NULL
     assert L.mxfp4_row_to_col(a16, a16, 32, 128, None, a16, None) == binding.ERR_NULL
     assert L.mxfp4_row_to_col_grouped(a16, a16, None, 2, 32, 128, a16, a16, None) == binding.ERR_NULL
+    assert L.mxfp4_row_to_fp8_col(a16, None, 128, 128, a16, a16, None) == binding.ERR_NULL
+    assert L.mxfp4_row_to_fp8_col_grouped(a16, a16, None, 2, 128, 128, a16, a16, None) == binding.ERR_NULL
     # alignment
     assert L.mxfp4_quant_from_fp8(odd, a16, 4, 128, None, 4, a16, 64, a16, 4, None) == binding.ERR_ALIGN
     assert L.mxfp4_quant_from_fp8(a16, a16, 4, 128, None, 4, a16, 68, a16, 4, None) == binding.ERR_ALIGN
     assert L.mxfp4_dequant_to_fp8(a16, 72, a16, 4, 4, 128, a16, a16, None) == binding.ERR_ALIGN
     assert L.mxfp4_row_to_col(a16, a16, 32, 128, odd, a16, None) == binding.ERR_ALIGN
+    assert L.mxfp4_row_to_fp8_col(a16, a16, 128, 128, odd, a16, None) == binding.ERR_ALIGN
+    assert L.mxfp4_row_to_fp8_col(a16, a16, 128, 128, a16, odd, None) == binding.ERR_ALIGN
     # expert count
     assert L.mxfp4_row_to_col_grouped(a16, a16, a16, 0, 32, 128, a16, a16, None) == binding.ERR_OFFSETS
     assert L.mxfp4_quant_from_fp8_grouped(a16, a16, a16, 5000, 32, 128, a16, a16, None) == binding.ERR_OFFSETS
@@ -58,3 +64,5 @@ def test_argument_validation_without_a_gpu():
     assert L.mxfp4_quant_from_fp8(None, None, 0, 128, None, 0, None, 64, None, 4, None) == binding.OK
     assert L.mxfp4_dequant_to_fp8(None, 64, None, 4, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_col(None, None, 0, 128, None, None, None) == binding.OK
+    assert L.mxfp4_row_to_fp8_col(None, None, 0, 128, None, None, None) == binding.OK
+    assert L.mxfp4_row_to_fp8_col_grouped(a16, a16, a16, 1025, 128, 128, a16, a16, None) == binding.ERR_OFFSETS

@@ -94,6 +94,29 @@ def test_target_row_to_col_65536x7168(target):
     assert_same(host(qc), wqc, "target column nibbles")
 
 
+def test_target_row_to_fp8_col_65536x7168(target):
+    x, xs = mx.mxfp4_row_to_fp8_col(target["q"], target["sf"])
+    wx, wxs = par.row_to_fp8_col(host(target["q"]), host(target["sf"]))
+    assert x.shape == (7168, 65536) and xs.shape == (7168, 512)
+    assert_same(host(xs), wxs, "target FP8 column group scales")
+    assert_same(host(x), wx, "target FP8 column bytes")
+
+
+def test_config4_grouped_row_to_fp8_col_32_experts():
+    off, counts = synth.expert_offsets(seed=3, num_experts=32, total_tokens=65536, pad_to=128)
+    M, K = int(off[-1]), 2048
+    y8, ys = synth.swiglu_fp8(M, K, seed=5, device=DEV)
+    y8, ys = synth.zero_padding_rows(y8, ys, off, counts)
+    rq, rsf = par.quant(host(y8), host(ys))
+    x, xs = mx.mxfp4_row_to_fp8_col_grouped(torch.from_numpy(rq).to(DEV), torch.from_numpy(rsf).to(DEV), off.to(DEV))
+    x, xs = host(x), host(xs)
+    for e in range(32):                                # per expert against the flat oracle routine
+        lo, hi = int(off[e]), int(off[e + 1])
+        wx, wxs = par.row_to_fp8_col(rq[lo:hi], rsf[lo:hi], workers=4)
+        assert_same(xs[K * lo // 128: K * hi // 128].reshape(K, (hi - lo) // 128), wxs, f"cfg4 expert {e} FP8 scales")
+        assert_same(x[K * lo: K * hi].reshape(K, hi - lo), wx, f"cfg4 expert {e} FP8 bytes")
+
+
 def test_config5_dispatch_payload_round_trip(target):
     x8, s = target["x8"], target["s"]
     M, K, top_k = 65536, 7168, 8

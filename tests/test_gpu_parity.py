@@ -290,3 +290,82 @@ def test_quant_bf16_activations_and_strides():
     recs = host(buf).reshape(200, rec)
     assert_same(recs[:, : K // 2], wq, "bf16 record nibbles")
     assert_same(recs[:, K // 2:], wsf, "bf16 record scales")
+
+
+# ------------------------------------------------------------------ row-blocked MXFP4 -> column-wise FP8
+
+def check_row_to_fp8_col(q, sf):
+    x, xs = mx.mxfp4_row_to_fp8_col(dev(q), dev(sf))
+    wx, wxs = ref.row_to_fp8_col(q, sf)
+    assert_same(host(xs), wxs, "row->FP8 col: group scales")
+    assert_same(host(x), wx, "row->FP8 col: E4M3 bytes")
+
+
+@pytest.mark.parametrize("M,K,center,spread,nan", [
+    (256, 256, 127, 0, 0.0), (384, 384, 127, 3, 0.0), (128, 128, 100, 8, 0.0), (640, 640, 30, 30, 0.0),
+    (128, 1152, 4, 6, 0.0), (384, 256, 250, 5, 0.0), (512, 512, 127, 127, 0.0), (384, 384, 120, 4, 0.003),
+    (256, 256, 120, 12, 0.05)])
+def test_row_to_fp8_col_random_codes_and_scale_spreads(M, K, center, spread, nan):
+    q, sf = synth.random_mxfp4(M, K, seed=M + K + spread, scale_center=center, scale_spread=spread,
+                               nan_scale_frac=nan)
+    q, sf = q.numpy().copy(), sf.numpy()
+    q[:, 5] = 0                                   # two all-zero columns
+    q[7::32, :] &= 0x88                           # rows of signed zeros
+    check_row_to_fp8_col(q, sf)
+
+
+def test_row_to_fp8_col_every_shift_and_code():
+    # row r of each 128-row group sits d = r binades under the group maximum (d = 0..127, then the same
+    # with larger steps down to byte 0); the 16 codes repeat along k; both halves of a 256-row tile differ
+    K = 256
+    nib = np.tile(np.arange(16, dtype=np.uint8), K // 16)
+    qrow = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+    qs, sfs = [], []
+    for bmax, step in ((254, 1), (140, 1), (254, 2), (41, 1), (20, 1), (6, 1), (3, 1), (0, 1)):
+        b = np.clip(bmax - step * np.arange(128), 0, 254).astype(np.uint8)
+        sf = np.repeat(b[:, None], K // 32, axis=1)
+        sf[:, 1] = b[::-1]                        # the maximum at the other end of the group
+        sf[:, 2] = np.roll(b, 37)
+        qs.append(np.repeat(qrow[None], 128, axis=0))
+        sfs.append(sf)
+    check_row_to_fp8_col(np.concatenate(qs), np.concatenate(sfs))
+
+
+def test_row_to_fp8_col_on_quantized_swiglu():
+    x8, s = synth.swiglu_fp8(1024, 2048, seed=1)
+    q, sf = par.quant(x8.numpy(), s.numpy())
+    check_row_to_fp8_col(q, sf)
+
+
+def test_row_to_fp8_col_grouped():
+    off = torch.tensor([0, 0, 384, 384, 512, 1152, 1152], dtype=torch.int32)
+    q, sf = synth.random_mxfp4(1152, 384, seed=6, scale_center=125, scale_spread=6, nan_scale_frac=0.001)
+    q, sf = q.numpy(), sf.numpy()
+    x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), off.to(DEV))
+    wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off.numpy())
+    assert_same(host(xs), wxs, "grouped row->FP8 col: group scales")
+    assert_same(host(x), wx, "grouped row->FP8 col: E4M3 bytes")
+    # one expert holding everything equals the flat call
+    one = torch.tensor([0, 1152], dtype=torch.int32)
+    x1, xs1 = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), one.to(DEV))
+    fx, fxs = ref.row_to_fp8_col(q, sf)
+    assert_same(host(xs1).reshape(fxs.shape), fxs, "single expert: group scales")
+    assert_same(host(x1).reshape(fx.shape), fx, "single expert: E4M3 bytes")
+
+
+def test_row_to_fp8_col_empty_and_argument_errors():
+    q = torch.zeros((0, 128), dtype=torch.uint8, device=DEV)
+    sf = torch.zeros((0, 8), dtype=torch.uint8, device=DEV)
+    x, xs = mx.mxfp4_row_to_fp8_col(q, sf)
+    assert x.shape == (256, 0) and xs.shape == (256, 0)
+    q = torch.zeros((96, 128), dtype=torch.uint8, device=DEV)
+    sf = torch.zeros((96, 8), dtype=torch.uint8, device=DEV)
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_row_to_fp8_col(q, sf)                                  # M % 128 != 0
+    assert e.value.status == -2
+    q = torch.zeros((128, 128), dtype=torch.uint8, device=DEV)
+    sf = torch.zeros((128, 8), dtype=torch.uint8, device=DEV)
+    xbuf = torch.zeros(256 * 128 + 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_row_to_fp8_col(q, sf, x_col=xbuf[1:1 + 256 * 128])     # misaligned output
+    assert e.value.status == -3
