@@ -100,7 +100,7 @@ mxfp4_status mxfp4_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t 
  * run of 32 consecutive m at fixed k is re-quantized with the rule of sec. 3.1.
  *   q_row [M, K/2] dense, 4-byte aligned;  sf_row [M, K/32] dense, 4-byte aligned
  *   q_col [K, M/2] dense, 16-byte aligned; sf_col [K, M/32] dense
- *   M % 32 == 0. */
+ *   M % 32 == 0; K at most 2^24. */
 mxfp4_status mxfp4_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
                               uint8_t *q_col, uint8_t *sf_col, void *hip_stream);
 
@@ -134,7 +134,7 @@ mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_ro
  * 0x7F; the other rows align to the maximum of the non-NaN bytes.
  *   q_row [M, K/2] dense, 4-byte aligned;  sf_row [M, K/32] dense, 4-byte aligned
  *   x_col E4M3 [K, M] dense, 16-byte aligned;  x_col_scale FP32 [K, M/128] dense, 4-byte aligned
- *   M % 128 == 0. */
+ *   M % 128 == 0; M and K at most 2^24. */
 mxfp4_status mxfp4_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
                                   uint8_t *x_col, float *x_col_scale, void *hip_stream);
 

@@ -133,8 +133,8 @@ static mxfp4_status row_to_fp8_col_common(const uint8_t *q_row, const uint8_t *s
         return MXFP4_OK;
     if (!q_row || !sf_row || !x_col || !x_col_scale)
         return MXFP4_ERR_NULL;
-    // byte offsets inside a 256-row tile are 32-bit, and so is the tile count
-    if (M >= kMaxRows || K > ((int64_t)1 << 24) ||
+    // byte offsets inside a 256 x 256 tile are 32-bit on both sides, and so is the tile count
+    if (M > ((int64_t)1 << 24) || K > ((int64_t)1 << 24) ||
         ((M + 255) / 256 + num_experts) * ((K + 255) / 256) >= ((int64_t)1 << 31))
         return MXFP4_ERR_SHAPE;
     if (!aligned(q_row, 4) || !aligned(sf_row, 4) || !aligned(x_col, 16) || !aligned(x_col_scale, 4) ||

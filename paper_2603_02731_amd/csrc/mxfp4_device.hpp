@@ -89,7 +89,7 @@ __device__ __forceinline__ uint32_t ue8m0_of_block_max(uint32_t gmax_bits)
 // and their few-byte scale pieces complete whole lines in that L2) and along k (they share the
 // 32-byte sectors of the row scales).  Returns false for the ids that round the grid up.
 constexpr uint32_t NUM_XCD = 8;
-template <uint32_t MBM, uint32_t MBK>
+template <uint32_t MBM, uint32_t MBK, bool K_FASTEST = false>
 __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
                                                   uint32_t *tile_m, uint32_t *tile_k)
 {
@@ -104,9 +104,16 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
     const uint32_t mb_rows = min(MBM, tiles_m - mg * MBM);
     const uint32_t kg = rem / (MBK * mb_rows);
     const uint32_t rem2 = rem - kg * MBK * mb_rows;
-    const uint32_t k_in = rem2 / mb_rows;
-    *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
-    *tile_k = kg * MBK + k_in;
+    if (K_FASTEST) { // inside a macro block walk k first
+        const uint32_t kw = min(MBK, tiles_k - kg * MBK);
+        const uint32_t m_in = rem2 / kw;
+        *tile_m = mg * MBM + m_in;
+        *tile_k = kg * MBK + (rem2 - m_in * kw);
+    } else {
+        const uint32_t k_in = rem2 / mb_rows;
+        *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
+        *tile_k = kg * MBK + k_in;
+    }
     return true;
 }
 

@@ -24,8 +24,11 @@
 
 namespace mxfp4 {
 
+#ifndef MXFP4_F8C_RPL
+#define MXFP4_F8C_RPL 32
+#endif
 #ifndef MXFP4_F8C_PHASES
-#define MXFP4_F8C_PHASES 2
+#define MXFP4_F8C_PHASES 1
 #endif
 #ifndef MXFP4_F8C_MBM
 #define MXFP4_F8C_MBM 32
@@ -33,18 +36,30 @@ namespace mxfp4 {
 #ifndef MXFP4_F8C_MBK
 #define MXFP4_F8C_MBK 4
 #endif
+#ifndef MXFP4_F8C_KFAST
+#define MXFP4_F8C_KFAST 0
+#endif
 #ifndef MXFP4_F8C_WAVES
 #define MXFP4_F8C_WAVES 1
+#endif
+#ifndef MXFP4_F8C_NT
+#define MXFP4_F8C_NT 1
 #endif
 
 namespace fp8col {
 
-constexpr int NRG = 8;              // 32-row groups per tile
-constexpr int T_THREADS = 32 * NRG; // one lane per (row group, 8-column group)
-constexpr int TILE_M = 32 * NRG;
+constexpr int RPL = MXFP4_F8C_RPL;       // rows of a lane's slice: 32, or 16 for twice the lanes per tile
+constexpr int TILE_M = 256;
 constexpr int TILE_K = 256;
+constexpr int LRG = TILE_M / RPL;        // lane row groups per tile
+constexpr int T_THREADS = 32 * LRG;      // one lane per (row group, 8-column group)
+constexpr int PARTS = T_THREADS / 256;   // threads per row while staging the row scales
+constexpr int KBT = 8 / PARTS;           // k-blocks a thread stages
+constexpr int SPL = RPL / 16;            // 16-byte output slots of a lane per column
 constexpr int PHASES = MXFP4_F8C_PHASES; // the tile leaves in PHASES parts of 8/PHASES columns per lane
 constexpr int CP = 8 / PHASES;           // columns of a lane per phase
+constexpr int HALVES = 512 / T_THREADS;  // copy-out passes per LDS k-row index range of 32
+static_assert(RPL == 16 || RPL == 32, "a lane owns one or two 16-byte output slots per column");
 static_assert(PHASES == 1 || PHASES == 2 || PHASES == 4, "a phase is a whole number of nibble bytes");
 
 typedef short s16x2 __attribute__((ext_vector_type(2)));
@@ -65,17 +80,19 @@ struct Args {
 // Decode-scale operand of row I of a slice: exponent field max(127 - (bmax - b_I), 0) in bits
 // 30:23, computed as a signed value so that one max() does the clamp.
 template <int I>
-__device__ __forceinline__ float row_shift_operand(const uint32_t (&sb)[8], int bias_minus_bmax)
+__device__ __forceinline__ float row_shift_operand(const uint32_t (&sb)[RPL / 4], int bias_minus_bmax)
 {
     const int b = (int)((sb[I >> 2] >> (8 * (I & 3))) & 0xFFu);
     return u2f((uint32_t)max((int)((uint32_t)(b + bias_minus_bmax) << 23), 0));
 }
 
-// 0xFF in every byte of `bytes4` that equals 0xFF.
-__device__ __forceinline__ uint32_t nan_byte_mask(uint32_t bytes4)
+// Maximum of the 8 bytes at p (8-byte aligned, LDS).
+__device__ __forceinline__ uint32_t max_of_8_bytes(const uint8_t *p)
 {
-    const uint32_t top = ((bytes4 & 0x7F7F7F7Fu) + 0x01010101u) & bytes4 & 0x80808080u;
-    return (top >> 7) * 0xFFu;
+    const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+    const uint32_t t = max(max(v.x & 0xFFu, (v.x >> 8) & 0xFFu), max((v.x >> 16) & 0xFFu, v.x >> 24));
+    const uint32_t u = max(max(v.y & 0xFFu, (v.y >> 8) & 0xFFu), max((v.y >> 16) & 0xFFu, v.y >> 24));
+    return max(t, u);
 }
 
 } // namespace fp8col
@@ -87,10 +104,10 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     __shared__ u32x4 s_out[(TILE_K / PHASES) * 16];      // [c'*32 + cg][16 slots]: k-rows of 256 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
     __shared__ alignas(8) uint8_t s_max16[8 * 16];       // [k-block][16-row group]: max of the non-NaN bytes
-    __shared__ uint8_t s_nan[4];                         // per wave: bit kb set = a NaN scale byte
+    __shared__ uint8_t s_nan[4 * 8];                     // [64-row group][k-block]: a NaN scale byte occurs
 
     uint32_t tile_m, tile_k;
-    if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k))
+    if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k))
         return;
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
@@ -114,8 +131,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
     if (m0 >= rows)
         return;
-    const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present: 4 or 8
-    const uint32_t n_g = n_rg / 4u;                              // 128-row scale groups present
+    const uint32_t n_rows = min((uint32_t)TILE_M, rows - m0) & ~127u; // rows present: 128 or 256
+    const uint32_t n_g = n_rows / 128u;                               // 128-row scale groups present
     const uint32_t k0 = tile_k * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
@@ -126,73 +143,73 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     const size_t pitch_x = rows, pitch_s = rows / 128u;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t rg = tid >> 5, cg = tid & 31u;
+    const uint32_t rgl = tid >> 5, cg = tid & 31u;
     const uint32_t pitch = a.K / 2u;
-    const bool active = rg < n_rg && cg * 8u < cols;
+    const bool active = rgl * RPL < n_rows && cg * 8u < cols;
 
-    // ---- the 32x8 slice of a lane: one dword (8 nibbles) per row
-    uint32_t w[32];
+    // ---- the RPL x 8 slice of a lane: one dword (8 nibbles) per row, from a uniform row pointer
+    // plus a 32-bit lane offset (one address register, not RPL pairs)
+    uint32_t w[RPL];
     if (active) {
-        const uint8_t *src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u + rg * 32u * pitch + cg * 4u;
+        const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
+        const uint32_t lane_off = rgl * RPL * pitch + cg * 4u; // < 2^32: K is at most 2^24
 #pragma unroll
-        for (int i = 0; i < 32; ++i)
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src + (size_t)i * pitch));
+        for (int i = 0; i < RPL; ++i)
+            w[i] = __builtin_nontemporal_load(
+                reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
     }
 
-    // ---- stage the tile's row scales (thread t takes row t, 4 or 8 bytes) and reduce them:
-    // per k-block the maximum of the non-NaN bytes over each 16 rows (DPP), and per wave
-    // whether a NaN byte occurs.
+    // ---- stage the tile's row scales (PARTS threads per row, KBT bytes each) and reduce them:
+    // per k-block the maximum of the non-NaN bytes over each 16 rows (DPP), and per 64 rows
+    // (a wave) whether a NaN byte occurs.
     {
-        uint32_t lo = 0, hi = 0;
-        if (tid < n_rg * 32u) {
-            const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
-            if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
-                const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
-                lo = v.x;
-                hi = v.y;
-            } else {
-                lo = reinterpret_cast<const uint32_t *>(p)[0];
-                hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
+        const uint32_t row = tid & 255u, part = tid >> 8;
+        uint32_t v[2] = {0u, 0u};
+        if (row < n_rows) {
+            const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + row) * Kb + k0 / 32u;
+            if (PARTS == 1) {
+                if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
+                    const u32x2 t = *reinterpret_cast<const u32x2 *>(p);
+                    v[0] = t.x;
+                    v[1] = t.y;
+                } else {
+                    v[0] = reinterpret_cast<const uint32_t *>(p)[0];
+                    v[1] = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
+                }
+            } else if (part == 0u || cols > 128u) {
+                v[0] = reinterpret_cast<const uint32_t *>(p)[part];
             }
         }
-        uint32_t nan_bits = 0, m_lo = 0, m_hi = 0;
+        uint32_t mx[2] = {0u, 0u}, nan_bits = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
-            s_row_sf[j * TILE_M + tid] = (uint8_t)b;
+        for (int j = 0; j < KBT; ++j) {
+            const uint32_t b = (v[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+            s_row_sf[(part * KBT + j) * TILE_M + row] = (uint8_t)b;
             nan_bits |= (__ballot(b == 255u) != 0ull ? 1u : 0u) << j;
-            uint32_t v = b == 255u ? 0u : b;
-            v = max(v, dpp_read<DPP_QUAD_XOR1>(v));
-            v = max(v, dpp_read<DPP_QUAD_XOR2>(v));
-            v = max(v, dpp_read<DPP_ROW_HALF_MIRROR>(v));
-            v = max(v, dpp_read<DPP_ROW_MIRROR>(v));
-            if (j < 4)
-                m_lo |= v << (8 * j);
-            else
-                m_hi |= v << (8 * (j - 4));
+            uint32_t t = b == 255u ? 0u : b;
+            t = max(t, dpp_read<DPP_QUAD_XOR1>(t));
+            t = max(t, dpp_read<DPP_QUAD_XOR2>(t));
+            t = max(t, dpp_read<DPP_ROW_HALF_MIRROR>(t));
+            t = max(t, dpp_read<DPP_ROW_MIRROR>(t));
+            mx[j >> 2] |= t << (8 * (j & 3));
         }
         if ((tid & 15u) == 0u) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                s_max16[j * 16 + (tid >> 4)] = (uint8_t)(m_lo >> (8 * j));
-                s_max16[(4 + j) * 16 + (tid >> 4)] = (uint8_t)(m_hi >> (8 * j));
-            }
+            for (int j = 0; j < KBT; ++j)
+                s_max16[(part * KBT + j) * 16 + (row >> 4)] = (uint8_t)(mx[j >> 2] >> (8 * (j & 3)));
         }
-        if ((tid & 63u) == 0u)
-            s_nan[tid >> 6] = (uint8_t)nan_bits;
+        if ((tid & 63u) == 0u) {
+#pragma unroll
+            for (int j = 0; j < KBT; ++j)
+                s_nan[(row >> 6) * 8 + part * KBT + j] = (uint8_t)((nan_bits >> j) & 1u);
+        }
     }
     __syncthreads();
 
     // ---- the lane's view: its k-block kb, its 128-row group g
-    const uint32_t kb = cg >> 2, g = rg >> 2;
-    uint32_t bmax;
-    {
-        const u32x2 p = *reinterpret_cast<const u32x2 *>(&s_max16[kb * 16 + g * 8]);
-        uint32_t t = max(max(p.x & 0xFFu, (p.x >> 8) & 0xFFu), max((p.x >> 16) & 0xFFu, p.x >> 24));
-        uint32_t u = max(max(p.y & 0xFFu, (p.y >> 8) & 0xFFu), max((p.y >> 16) & 0xFFu, p.y >> 24));
-        bmax = max(t, u);
-    }
-    const bool has_nan = (((s_nan[2 * g] | s_nan[2 * g + 1]) >> kb) & 1u) != 0u;
+    const uint32_t kb = cg >> 2, g = (rgl * RPL) >> 7;
+    const uint32_t bmax = max_of_8_bytes(&s_max16[kb * 16 + g * 8]);
+    const bool has_nan = (s_nan[(2 * g) * 8 + kb] | s_nan[(2 * g + 1) * 8 + kb]) != 0u;
 
     // ---- group scales: k-row t of the tile, one float per 128-row group
     if (tid < cols) {
@@ -200,12 +217,10 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         uint32_t bits[2];
 #pragma unroll
         for (int gg = 0; gg < 2; ++gg) {
-            const u32x2 p = *reinterpret_cast<const u32x2 *>(&s_max16[kbt * 16 + gg * 8]);
-            const uint32_t t = max(max(p.x & 0xFFu, (p.x >> 8) & 0xFFu), max((p.x >> 16) & 0xFFu, p.x >> 24));
-            const uint32_t u = max(max(p.y & 0xFFu, (p.y >> 8) & 0xFFu), max((p.y >> 16) & 0xFFu, p.y >> 24));
-            const int e = (int)max(t, u) - 6; // biased exponent of 2^(max - 6 - 127); below 1: an FP32 subnormal
+            // biased exponent of 2^(max - 6 - 127); below 1: an FP32 subnormal
+            const int e = (int)max_of_8_bytes(&s_max16[kbt * 16 + gg * 8]) - 6;
             bits[gg] = e >= 1 ? (uint32_t)e << 23 : 0x00400000u >> (uint32_t)(-e);
-            if ((((s_nan[2 * gg] | s_nan[2 * gg + 1]) >> kbt) & 1u) != 0u)
+            if ((s_nan[(2 * gg) * 8 + kbt] | s_nan[(2 * gg + 1) * 8 + kbt]) != 0u)
                 bits[gg] = 0x7FC00000u;
         }
         float *dst = out_s + (size_t)(k0 + tid) * pitch_s + m0 / 128u;
@@ -219,78 +234,101 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         }
     }
 
-    // ---- the 32 row-scale bytes of this slice (byte i%4 of dword i/4 is row i) -> decode operands
-    uint32_t sb[8];
-    float dsc[32];
+    // ---- the row-scale bytes of this slice (byte i%4 of dword i/4 is row i) -> decode operands
+    uint32_t sb[RPL / 4];
+    float dsc[RPL];
+    const uint8_t *my_row_sf = &s_row_sf[kb * TILE_M + rgl * RPL];
     if (active) {
-        const uint8_t *my_row_sf = &s_row_sf[kb * TILE_M + rg * 32u];
-        const u32x4 s0 = reinterpret_cast<const u32x4 *>(my_row_sf)[0];
-        const u32x4 s1 = reinterpret_cast<const u32x4 *>(my_row_sf)[1];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            sb[q] = s0[q];
-            sb[4 + q] = s1[q];
+        for (int h = 0; h < SPL; ++h) {
+            const u32x4 t = reinterpret_cast<const u32x4 *>(my_row_sf)[h];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                sb[4 * h + q] = t[q];
         }
         const int bias_minus_bmax = 127 - (int)bmax;
-        static_for<32>([&](auto ip) {
+        static_for<RPL>([&](auto ip) {
             constexpr int i = decltype(ip)::value;
             dsc[i] = row_shift_operand<i>(sb, bias_minus_bmax);
         });
     }
     const float enc = u2f(121u << 23); // the encoder divides by 2^-6: Algorithm 1's delta
 
-    const uint32_t slot0 = (2u * rg + cg) & 15u; // 16-byte slots of rows 0..15 / 16..31 of the slice
-    const uint32_t slot1 = (2u * rg + 1u + cg) & 15u;
+    // 16-byte slot h of the slice (its rows 16h..16h+15) goes to physical slot (logical + cg) % 16
+    uint32_t slot[SPL];
+#pragma unroll
+    for (int h = 0; h < SPL; ++h)
+        slot[h] = (rgl * SPL + h + cg) & 15u;
 
     static_for<PHASES>([&](auto php) {
         constexpr int ph = decltype(php)::value;
         if (active) {
             static_for<CP / 2>([&](auto jjp) {
                 constexpr int j = ph * (CP / 2) + decltype(jjp)::value; // nibble byte: columns 2j, 2j+1
-                uint32_t o[2][8];
-                static_for<8>([&](auto rp) {
+                uint32_t o[2][RPL / 4];
+                static_for<RPL / 4>([&](auto rp) {
                     constexpr int r = decltype(rp)::value; // rows 4r..4r+3 -> dword r of both columns
                     const f32x2 f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[4 * r], dsc[4 * r], j);
                     const f32x2 f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[4 * r + 1], dsc[4 * r + 1], j);
                     const f32x2 f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[4 * r + 2], dsc[4 * r + 2], j);
                     const f32x2 f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[4 * r + 3], dsc[4 * r + 3], j);
-                    s16x2 e0 = {0, 0}, e1 = {0, 0};
+                    s16x2 e0, e1; // no initial value needed: both words are written
+                    asm volatile("" : "=v"(e0), "=v"(e1));
                     e0 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(e0, f0.x, f1.x, enc, false);
                     e0 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(e0, f2.x, f3.x, enc, true);
                     e1 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(e1, f0.y, f1.y, enc, false);
                     e1 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(e1, f2.y, f3.y, enc, true);
                     o[0][r] = __builtin_bit_cast(uint32_t, e0);
                     o[1][r] = __builtin_bit_cast(uint32_t, e1);
-                    if (has_nan) { // rare: rows under a NaN scale byte become E4M3 NaN
-                        const uint32_t nm = nan_byte_mask(sb[r]);
-                        o[0][r] = (o[0][r] & ~nm) | (0x7F7F7F7Fu & nm);
-                        o[1][r] = (o[1][r] & ~nm) | (0x7F7F7F7Fu & nm);
-                    }
                 });
 #pragma unroll
                 for (int cc = 0; cc < 2; ++cc) {
                     const uint32_t row = ((2 * j + cc) - ph * CP) * 32u + cg; // LDS k-row of column 2j+cc
-                    s_out[row * 16u + slot0] = u32x4{o[cc][0], o[cc][1], o[cc][2], o[cc][3]};
-                    s_out[row * 16u + slot1] = u32x4{o[cc][4], o[cc][5], o[cc][6], o[cc][7]};
+#pragma unroll
+                    for (int h = 0; h < SPL; ++h)
+                        s_out[row * 16u + slot[h]] =
+                            u32x4{o[cc][4 * h], o[cc][4 * h + 1], o[cc][4 * h + 2], o[cc][4 * h + 3]};
                 }
             });
+            if (has_nan) {
+                // rare: the rows under a NaN scale byte become E4M3 NaN; patched byte by byte in the
+                // lane's own LDS slots (rolled: this path is written for size, not speed)
+                uint8_t *bytes = reinterpret_cast<uint8_t *>(s_out);
+#pragma nounroll
+                for (uint32_t i = 0; i < (uint32_t)RPL; ++i) {
+                    if (my_row_sf[i] != 255u)
+                        continue;
+                    const uint32_t sl = (rgl * SPL + (i >> 4) + cg) & 15u;
+#pragma nounroll
+                    for (uint32_t c = 0; c < (uint32_t)CP; ++c)
+                        bytes[((c * 32u + cg) * 16u + sl) * 16u + (i & 15u)] = 0x7Fu;
+                }
+            }
         }
         __syncthreads();
 
-        // ---- write the part out: 16 lanes per k-row, 256 contiguous bytes.  Chunk u*256 + tid of
-        // the LDS part is row u*16 + tid/16 = c'*32 + cgx, physical slot tid%16.
+        // ---- write the part out: 16 lanes per k-row, 256 contiguous bytes.  Chunk u*T + tid of the
+        // LDS part is row c'*32 + cgx, physical slot tid%16, with cgx = tid/16 (plus 16 in the odd
+        // passes when T = 256).  Uniform k-row pointers plus one 32-bit lane offset (M <= 2^24).
         {
             const uint32_t pslot = tid & 15u;
+            const uint32_t lslot = (pslot - (tid >> 4)) & 15u; // 16 bytes = rows 16*lslot.. of the tile
+            const uint32_t lane_off = (tid >> 4) * 8u * (uint32_t)pitch_x + lslot * 16u;
+            uint8_t *krow0 = out_x + (size_t)(k0 + ph * CP) * pitch_x + m0;
+            static_for<HALVES>([&](auto oddp) {
+                constexpr int odd = decltype(oddp)::value;
+                if ((odd * 16u + (tid >> 4)) * 8u < cols && lslot * 16u < n_rows) {
 #pragma unroll
-            for (int u = 0; u < 2 * CP; ++u) {
-                const uint32_t cgx = (u & 1) * 16u + (tid >> 4);
-                const uint32_t c = ph * CP + (u >> 1);
-                const uint32_t lslot = (pslot - cgx) & 15u; // 16 bytes = rows 16*lslot.. of the tile
-                if (cgx * 8u < cols && (lslot >> 1) < n_rg) {
-                    uint8_t *dst = out_x + (size_t)(k0 + cgx * 8u + c) * pitch_x + m0 + lslot * 16u;
-                    *reinterpret_cast<u32x4 *>(dst) = s_out[u * T_THREADS + tid];
+                    for (int c = 0; c < CP; ++c) {
+                        u32x4 *dst = reinterpret_cast<u32x4 *>(krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off);
+#if MXFP4_F8C_NT
+                        __builtin_nontemporal_store(s_out[(HALVES * c + odd) * T_THREADS + tid], dst);
+#else
+                        *dst = s_out[(HALVES * c + odd) * T_THREADS + tid];
+#endif
+                    }
                 }
-            }
+            });
         }
         if (ph + 1 < PHASES)
             __syncthreads(); // the LDS part is free again
