@@ -29,11 +29,8 @@ namespace mxfp4 {
 #ifndef MXFP4_RTC_NRG
 #define MXFP4_RTC_NRG 8
 #endif
-#ifndef MXFP4_RTC_PM
-#define MXFP4_RTC_PM 1
-#endif
 #ifndef MXFP4_RTC_MBM
-#define MXFP4_RTC_MBM (32 / MXFP4_RTC_PM)
+#define MXFP4_RTC_MBM 32
 #endif
 #ifndef MXFP4_RTC_MBK
 #define MXFP4_RTC_MBK 4
@@ -45,10 +42,7 @@ constexpr int NRG = MXFP4_RTC_NRG;  // 32-row groups per tile
 constexpr int T_THREADS = 32 * NRG; // one lane per (row group, 8-column group)
 constexpr int TILE_M = 32 * NRG;
 constexpr int TILE_K = 256;
-constexpr int PM = MXFP4_RTC_PM;      // consecutive row tiles per workgroup
-constexpr int STRIP_M = TILE_M * PM;  // rows per workgroup
 static_assert(NRG == 8, "the LDS slot swizzle and the copy-out assume 8 row groups");
-static_assert(TILE_K * PM * NRG <= TILE_K * NRG * 16, "the column scales of a strip fit the tile buffer");
 
 struct RowToColArgs {
     const uint8_t *q_row;
@@ -59,7 +53,7 @@ struct RowToColArgs {
     int32_t num_experts;
     uint32_t M; // total rows
     uint32_t K;
-    uint32_t tiles_m; // row strips of PM tiles (an upper bound when grouped)
+    uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
 };
 
@@ -189,18 +183,20 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
     return col_bytes;
 }
 
-// A workgroup walks PM consecutive 256-row tiles of one 256-column strip, so that each k-row's
-// column-scale bytes leave as ONE request of PM*8 bytes (the scale planes are 1/17 of the bytes
-// but, moved 8 bytes at a time, cost about a fifth of the kernel's time); the nibbles of the
-// next tile are requested before the current one is written out.  Measured at [65536,7168]:
-// PM = 1: 98 us, 2: 94-97 us, 4: 113 us, 8: 130 us -- fewer, longer workgroups overlap worse
-// than the saved requests gain, so PM = 1 is built.
+// One tile per workgroup and two barriers: the column scales get their own 2 KiB of LDS, so that
+// after the conversion the scale bytes and the nibbles leave without further synchronisation
+// (measured at [65536,7168]: 93 us against 98 us with the scales staged over the tile buffer
+// behind two more barriers).  Also measured and not built: walking 2/4/8 row tiles per workgroup
+// with one column-scale request per k-row (94-97 / 113 / 130 us: fewer, longer workgroups
+// overlap worse than the saved requests gain), 512-row tiles (100 us, with or without
+// non-temporal stores), non-temporal stores for the 128-byte output rows (97 us), requesting the
+// row scales before the nibbles (no difference).
 __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
 {
     __shared__ u32x4 s_out[TILE_K * NRG];                // [c*32 + cg][slot]: 256 k-rows x 128 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
+    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [k][row group]
     __shared__ uint8_t s_special[NRG];                   // per row group: bit kb set = a scale byte >= 253
-    uint8_t *s_col_sf = reinterpret_cast<uint8_t *>(s_out); // [k][PM*NRG], after the last tile is out
 
     uint32_t strip, tile_k;
     if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k))
@@ -212,7 +208,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         bool found = false;
         for (int e = 0; e < a.num_experts; ++e) {
             const uint32_t lo = (uint32_t)a.expert_offsets[e], hi = (uint32_t)a.expert_offsets[e + 1];
-            const uint32_t nt = (hi - lo + STRIP_M - 1) / STRIP_M;
+            const uint32_t nt = (hi - lo + TILE_M - 1) / TILE_M;
             if (strip < nt) {
                 row_base = lo;
                 rows = hi - lo;
@@ -224,10 +220,10 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         if (!found)
             return;
     }
-    const uint32_t mm0 = strip * STRIP_M; // first row of the strip inside its group
-    if (mm0 >= rows)
+    const uint32_t m0 = strip * TILE_M;
+    if (m0 >= rows)
         return;
-    const uint32_t strip_rg = min((uint32_t)STRIP_M, rows - mm0) / 32u; // row groups in the strip
+    const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
     const uint32_t k0 = tile_k * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
@@ -243,14 +239,30 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     // results go to LDS row (c*32 + cg), 16-byte slot rotated by the column group, so that
     // consecutive lanes write different banks and the read-back is linear
     const uint32_t slot = (rg + (cg >> 1)) & (NRG - 1u);
-    const uint32_t lane_off = rg * 32u * pitch + cg * 4u; // < 2^32: K is at most 2^24
+    const uint32_t lane_off = rg * 32u * pitch + cg * 4u;
+    const bool active = rg < n_rg && cg * 8u < cols;
 
-    // the 32x8 slice of a lane: one dword (8 nibbles) per row, from a uniform row pointer plus
-    // a 32-bit lane offset (one address register, not 32 pairs)
+    // the tile's row scales: thread t takes row t, one 8-byte request where the layout allows it
+    // (K % 256 == 0), else 4 + 4
+    uint32_t lo = 0, hi = 0;
+    auto load_sf = [&]() {
+        if (tid < n_rg * 32u) {
+            const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
+            if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
+                const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+                lo = v.x;
+                hi = v.y;
+            } else {
+                lo = reinterpret_cast<const uint32_t *>(p)[0];
+                hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
+            }
+        }
+    };
+    // the 32x8 slice of a lane: one dword (8 nibbles) per row, from a uniform row pointer plus a
+    // 32-bit lane offset (one address register, not 32 pairs)
     uint32_t w[32];
-    auto load_slice = [&](uint32_t m0) {
-        const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u;
-        if (rg < n_rg && cg * 8u < cols) {
+    auto load_slice = [&]() {
+        if (active) {
             const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
 #pragma unroll
             for (int i = 0; i < 32; ++i)
@@ -258,147 +270,104 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
                     reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
         }
     };
-    load_slice(mm0);
-
-    uint64_t col_bytes[PM]; // this lane's 8 column-scale bytes of every tile of the strip
-
-    static_for<PM>([&](auto msp) {
-        constexpr int ms = decltype(msp)::value;
-        const uint32_t m0 = mm0 + ms * TILE_M;
-        col_bytes[ms] = 0;
-        if (m0 < rows) { // uniform
-            const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
-            const bool active = rg < n_rg && cg * 8u < cols;
-
-            // ---- stage the tile's row scales: thread t takes row t, 4 or 8 bytes.  A wave stages
-            // two row groups; one ballot per k-block tells which (row group, k-block) pairs hold
-            // a byte of 253 or more (beyond FP32, or NaN).
-            {
-                uint32_t lo = 0, hi = 0;
-                if (tid < n_rg * 32u) {
-                    // one 8-byte request per row where the layout allows it (K % 256 == 0), else 4 + 4
-                    const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
-                    if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
-                        const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
-                        lo = v.x;
-                        hi = v.y;
-                    } else {
-                        lo = reinterpret_cast<const uint32_t *>(p)[0];
-                        hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
-                    }
+    load_slice();
+    load_sf();
+    // ---- stage the row scales.  A wave stages two row groups; one ballot per k-block tells which
+    // (row group, k-block) pairs hold a byte of 253 or more (beyond FP32, or NaN).
+    {
+        if (tid < n_rg * 32u) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
-                        s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
-                    }
-                }
-                uint32_t special_lo = 0, special_hi = 0; // bit kb: first / second row group of this wave
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
-                    const uint64_t m = __ballot(b >= 253u);
-                    special_lo |= ((uint32_t)m != 0u ? 1u : 0u) << j;
-                    special_hi |= ((uint32_t)(m >> 32) != 0u ? 1u : 0u) << j;
-                }
-                if ((tid & 63u) == 0u) {
-                    s_special[(tid >> 6) * 2] = (uint8_t)special_lo;
-                    s_special[(tid >> 6) * 2 + 1] = (uint8_t)special_hi;
-                }
+            for (int j = 0; j < 4; ++j) {
+                s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
+                s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
             }
-            __syncthreads();
-
-            if (active) {
-                const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * TILE_M + rg * 32u];
-                if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
-                    // the 32 row-scale bytes of this slice: byte i%4 of dword i/4 is row i
-                    uint32_t sb[8];
-                    const u32x4 s0 = reinterpret_cast<const u32x4 *>(my_row_sf)[0];
-                    const u32x4 s1 = reinterpret_cast<const u32x4 *>(my_row_sf)[1];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        sb[g] = s0[g];
-                        sb[4 + g] = s1[g];
-                    }
-                    uint32_t cb[8];   // column scale bytes
-                    uint32_t o[8][4]; // per column: 32 output nibbles (rows 0..31 of the slice)
-                    requant_slice_hw(w, sb, cb, o);
-                    uint32_t cb_lo = 0, cb_hi = 0;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c)
-                        s_out[(c * 32 + cg) * NRG + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        cb_lo |= cb[c] << (8 * c);
-                        cb_hi |= cb[4 + c] << (8 * c);
-                    }
-                    col_bytes[ms] = ((uint64_t)cb_hi << 32) | cb_lo;
-                } else {
-                    bool poisoned = false; // a NaN row scale touches all 8 columns of the slice
-                    for (int i = 0; i < 32; ++i)
-                        poisoned |= my_row_sf[i] == 255u;
-                    if (poisoned) {
-#pragma unroll
-                        for (int c = 0; c < 8; ++c)
-                            s_out[(c * 32 + cg) * NRG + slot] = u32x4{0u, 0u, 0u, 0u};
-                        col_bytes[ms] = ~(uint64_t)0;
-                    } else {
-                        const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
-                        col_bytes[ms] = requant_slice_int(tile_src + lane_off, pitch, my_row_sf,
-                                                          reinterpret_cast<uint32_t *>(&s_out[cg * NRG + slot]),
-                                                          32 * NRG * 4);
-                    }
-                }
-            }
-            __syncthreads();
-
-            // ---- request the next tile's nibbles, then write this tile out: 8 lanes per k-row,
-            // 128 contiguous bytes each.  Chunk f = u*256 + tid of the LDS tile is row
-            // (u*32 + tid/8), slot tid%8: column k = (tid/8)*8 + u.
-            if (ms + 1 < PM && m0 + TILE_M < rows)
-                load_slice(m0 + TILE_M);
-            {
-                const uint32_t cgx = tid / NRG;
-                const uint32_t part = ((tid & (NRG - 1u)) - (cgx >> 1)) & (NRG - 1u); // row group in this slot
-                uint8_t *dst = out_q + (size_t)(k0 + cgx * 8u) * pitch_q + m0 / 2u + part * 16u;
-                if (cgx * 8u < cols && part < n_rg) {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
-                }
-            }
-            __syncthreads(); // the LDS tile and the staged row scales are free again
         }
-    });
-
-    // ---- column scales of the strip: through LDS (over the tile buffer) into k-rows
-    if (cg * 8u < cols) {
-        static_for<PM>([&](auto msp) {
-            constexpr int ms = decltype(msp)::value;
+        uint32_t special_lo = 0, special_hi = 0;
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
-                s_col_sf[(cg * 8 + c) * (PM * NRG) + ms * NRG + rg] = (uint8_t)(col_bytes[ms] >> (8 * c));
-        });
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
+            const uint64_t m = __ballot(b >= 253u);
+            special_lo |= ((uint32_t)m != 0u ? 1u : 0u) << j;
+            special_hi |= ((uint32_t)(m >> 32) != 0u ? 1u : 0u) << j;
+        }
+        if ((tid & 63u) == 0u) {
+            s_special[(tid >> 6) * 2] = (uint8_t)special_lo;
+            s_special[(tid >> 6) * 2 + 1] = (uint8_t)special_hi;
+        }
     }
     __syncthreads();
+
+    if (active) {
+        const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * TILE_M + rg * 32u];
+        uint64_t col_bytes;
+        if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
+            uint32_t sb[8];
+            const u32x4 s0 = reinterpret_cast<const u32x4 *>(my_row_sf)[0];
+            const u32x4 s1 = reinterpret_cast<const u32x4 *>(my_row_sf)[1];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                sb[g] = s0[g];
+                sb[4 + g] = s1[g];
+            }
+            uint32_t cb[8];
+            uint32_t o[8][4];
+            requant_slice_hw(w, sb, cb, o);
+            uint32_t cb_lo = 0, cb_hi = 0;
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                s_out[(c * 32 + cg) * NRG + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                cb_lo |= cb[c] << (8 * c);
+                cb_hi |= cb[4 + c] << (8 * c);
+            }
+            col_bytes = ((uint64_t)cb_hi << 32) | cb_lo;
+        } else {
+            bool poisoned = false; // a NaN row scale touches all 8 columns of the slice
+            for (int i = 0; i < 32; ++i)
+                poisoned |= my_row_sf[i] == 255u;
+            if (poisoned) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    s_out[(c * 32 + cg) * NRG + slot] = u32x4{0u, 0u, 0u, 0u};
+                col_bytes = ~(uint64_t)0;
+            } else {
+                const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
+                col_bytes = requant_slice_int(tile_src + lane_off, pitch, my_row_sf,
+                                              reinterpret_cast<uint32_t *>(&s_out[cg * NRG + slot]), 32 * NRG * 4);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            s_col_sf[(cg * 8 + c) * NRG + rg] = (uint8_t)(col_bytes >> (8 * c));
+    }
+    __syncthreads();
+
+    // ---- out: the column scales as one request per k-row, then the nibbles, 8 lanes per k-row with
+    // 128 contiguous bytes each.  Chunk u*256 + tid of the LDS tile is row (u*32 + tid/8), slot
+    // tid%8: column k = (tid/8)*8 + u.  Both read LDS regions written before the one barrier above.
     if (tid < cols) {
-        // PM*8 bytes per k-row (fewer at the end of a group), in the widest pieces the address allows
-        uint8_t *dst = out_sf + (size_t)(k0 + tid) * pitch_sf + mm0 / 32u;
-        const uint8_t *src = &s_col_sf[tid * (PM * NRG)];
+        uint8_t *dst = out_sf + (size_t)(k0 + tid) * pitch_sf + m0 / 32u;
+        const uint8_t *src = &s_col_sf[tid * NRG];
         const uintptr_t al = reinterpret_cast<uintptr_t>(dst);
-        if ((strip_rg & 3u) == 0u && (al & 15u) == 0u) {
-            uint32_t g = 0;
-            for (; g + 16u <= strip_rg; g += 16u)
-                *reinterpret_cast<u32x4 *>(dst + g) = *reinterpret_cast<const u32x4 *>(src + g);
-            for (; g + 8u <= strip_rg; g += 8u)
-                *reinterpret_cast<u32x2 *>(dst + g) = *reinterpret_cast<const u32x2 *>(src + g);
-            for (; g < strip_rg; g += 4u)
-                *reinterpret_cast<uint32_t *>(dst + g) = *reinterpret_cast<const uint32_t *>(src + g);
-        } else if ((strip_rg & 3u) == 0u && (al & 3u) == 0u) {
-            for (uint32_t g = 0; g < strip_rg; g += 4u)
+        if (n_rg == 8u && (al & 7u) == 0u) {
+            *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<const u32x2 *>(src);
+        } else if ((n_rg & 3u) == 0u && (al & 3u) == 0u) {
+            for (uint32_t g = 0; g < n_rg; g += 4u)
                 *reinterpret_cast<uint32_t *>(dst + g) = *reinterpret_cast<const uint32_t *>(src + g);
         } else {
-            for (uint32_t g = 0; g < strip_rg; ++g)
+            for (uint32_t g = 0; g < n_rg; ++g)
                 dst[g] = src[g];
+        }
+    }
+    {
+        const uint32_t cgx = tid / NRG;
+        const uint32_t part = ((tid & (NRG - 1u)) - (cgx >> 1)) & (NRG - 1u);
+        uint8_t *dst = out_q + (size_t)(k0 + cgx * 8u) * pitch_q + m0 / 2u + part * 16u;
+        if (cgx * 8u < cols && part < n_rg) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
         }
     }
 }
@@ -416,8 +385,8 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.num_experts = num_experts;
     a.M = (uint32_t)M;
     a.K = (uint32_t)K;
-    // upper bound on the number of row strips: every expert may end in a partial one
-    a.tiles_m = (uint32_t)((M + STRIP_M - 1) / STRIP_M + (expert_offsets ? num_experts : 0));
+    // upper bound on the number of row tiles: every expert may end in a partial one
+    a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
