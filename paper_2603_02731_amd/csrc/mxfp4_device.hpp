@@ -117,6 +117,45 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
     return true;
 }
 
+// Ragged inputs: which expert owns row tile `tile` of the concatenation of all experts' tiles
+// (expert e contributes ceil(T_e / TILE_ROWS) tiles, T_e = off[e+1] - off[e]).  Uniform per
+// workgroup; every wave evaluates it on its own, 64 experts at a time: one coalesced load of the
+// offsets, a wave prefix sum of the tile counts and a ballot, instead of a serial scan whose
+// every step waits for memory.  On success `tile` becomes the tile index inside the expert.
+template <uint32_t TILE_ROWS>
+__device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_experts, uint32_t *tile,
+                                               uint32_t *row_base, uint32_t *rows)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t before = 0; // tiles of the experts in earlier chunks
+    for (int32_t base = 0; base < num_experts; base += 64) {
+        const int32_t e = base + (int32_t)lane;
+        uint32_t lo = 0, hi = 0;
+        if (e < num_experts) {
+            lo = (uint32_t)off[e];
+            hi = (uint32_t)off[e + 1];
+        }
+        const uint32_t nt = (hi - lo + TILE_ROWS - 1u) / TILE_ROWS;
+        uint32_t incl = nt; // inclusive prefix sum over the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
+            incl += lane >= (uint32_t)d ? up : 0u;
+        }
+        const uint64_t hit = __ballot(before + incl > *tile);
+        if (hit != 0ull) {
+            const int l = __ffsll((unsigned long long)hit) - 1;
+            const uint32_t excl = (uint32_t)__builtin_amdgcn_readlane((int)(incl - nt), l);
+            *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo, l);
+            *rows = (uint32_t)__builtin_amdgcn_readlane((int)(hi - lo), l);
+            *tile -= before + excl;
+            return true;
+        }
+        before += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    }
+    return false;
+}
+
 // Compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>).
 // The conversion builtins take their byte selector as an immediate.
 template <class F, int... I>

@@ -204,22 +204,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
     uint32_t row_base = 0, rows = a.M;
-    if (a.expert_offsets) {
-        bool found = false;
-        for (int e = 0; e < a.num_experts; ++e) {
-            const uint32_t lo = (uint32_t)a.expert_offsets[e], hi = (uint32_t)a.expert_offsets[e + 1];
-            const uint32_t nt = (hi - lo + TILE_M - 1) / TILE_M;
-            if (strip < nt) {
-                row_base = lo;
-                rows = hi - lo;
-                found = true;
-                break;
-            }
-            strip -= nt;
-        }
-        if (!found)
-            return;
-    }
+    if (a.expert_offsets && !tile_of_expert<TILE_M>(a.expert_offsets, a.num_experts, &strip, &row_base, &rows))
+        return;
     const uint32_t m0 = strip * TILE_M;
     if (m0 >= rows)
         return;

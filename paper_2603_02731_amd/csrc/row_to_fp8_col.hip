@@ -112,22 +112,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
 
     // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
     uint32_t row_base = 0, rows = a.M;
-    if (a.expert_offsets) {
-        bool found = false;
-        for (int e = 0; e < a.num_experts; ++e) {
-            const uint32_t lo = (uint32_t)a.expert_offsets[e], hi = (uint32_t)a.expert_offsets[e + 1];
-            const uint32_t nt = (hi - lo + TILE_M - 1) / TILE_M;
-            if (tile_m < nt) {
-                row_base = lo;
-                rows = hi - lo;
-                found = true;
-                break;
-            }
-            tile_m -= nt;
-        }
-        if (!found)
-            return;
-    }
+    if (a.expert_offsets && !tile_of_expert<TILE_M>(a.expert_offsets, a.num_experts, &tile_m, &row_base, &rows))
+        return;
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
     if (m0 >= rows)
         return;

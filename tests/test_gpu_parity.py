@@ -369,3 +369,24 @@ def test_row_to_fp8_col_empty_and_argument_errors():
     with pytest.raises(mx.Mxfp4Error) as e:
         mx.mxfp4_row_to_fp8_col(q, sf, x_col=xbuf[1:1 + 256 * 128])     # misaligned output
     assert e.value.status == -3
+
+
+def test_grouped_more_experts_than_a_wave():
+    # 150 experts (the lookup works on 64 at a time), many empty, sizes 0..5 blocks of 128 rows
+    rng = np.random.default_rng(12)
+    counts = rng.integers(0, 6, size=150) * 128
+    counts[rng.random(150) < 0.4] = 0
+    counts[[0, 63, 64, 127, 128, 149]] = [0, 256, 128, 0, 384, 128]
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    M, K = int(off[-1]), 256
+    q, sf = synth.random_mxfp4(M, K, seed=13, scale_center=124, scale_spread=5)
+    q, sf = q.numpy(), sf.numpy()
+    offd = torch.from_numpy(off).to(DEV)
+    qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd)
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off)
+    assert_same(host(sc), wsc, "150 experts row->col scales")
+    assert_same(host(qc), wqc, "150 experts row->col nibbles")
+    x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd)
+    wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off)
+    assert_same(host(xs), wxs, "150 experts row->FP8 col scales")
+    assert_same(host(x), wx, "150 experts row->FP8 col bytes")
