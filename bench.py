@@ -34,6 +34,9 @@ def parse():
                         "launch): the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
     p.add_argument("--variants", action="store_true",
                    help="also time the gathered, record-layout and grouped entry points (extra JSON field)")
+    p.add_argument("--variant", default=None,
+                   help="with --variants: time only the entry point of this name (e.g. row_to_fp8_col), "
+                        "so that a profiler run sees that kernel at one launch shape")
     return p.parse_args()
 
 
@@ -180,6 +183,9 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
     M, K = x8.shape
     res = {}
 
+    def want(name):
+        return a.variant is None or a.variant == name
+
     def timed(fn):
         for _ in range(2):
             fn()
@@ -191,58 +197,64 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
-    # the paper's BF16-source row quantizer on the same activations (2 B read + 0.53125 B written per element)
-    xbf = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
-    for r0 in range(0, M, 8192):
-        xbf[r0:r0 + 8192] = (x8[r0:r0 + 8192].view(torch.float8_e4m3fn).float()
-                             * s[r0:r0 + 8192].repeat_interleave(128, dim=1)).to(torch.bfloat16)
-    qb = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
-    sb = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
-    us = timed(lambda: mx.mxfp4_quant_from_bf16(xbf, q=qb, sf=sb))
-    b = M * K * (2.0 + 0.53125)
-    res["quant_from_bf16"] = {"us": us, "GB/s": b / us * 1e-3, "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
-    del xbf, qb, sb
+    def entry(us, nbytes, **extra):
+        return {**extra, "us": us, "GB/s": nbytes / us * 1e-3, "frac_of_hbm_peak": nbytes / us * 1e-3 / HBM_PEAK_GBPS}
 
-    top_k = 8
-    idx = synth.routing_indices(seed=a.seed, num_tokens=M, top_k=top_k, device=dev)
-    Mo = idx.shape[0]
-    qg = torch.empty((Mo, K // 2), dtype=torch.uint8, device=dev)
-    sg = torch.empty((Mo, K // 32), dtype=torch.uint8, device=dev)
-    us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=qg, sf=sg))
-    logical = Mo * K * BYTES_PER_ELEM["quant"]
-    compulsory = M * K * 1.03125 + Mo * 4 + Mo * K * 0.53125
-    res["quant_gather_top8"] = {"us": us, "logical_GB/s": logical / us * 1e-3,
-                                "compulsory_GB/s": compulsory / us * 1e-3,
-                                "frac_of_hbm_peak_compulsory": compulsory / us * 1e-3 / HBM_PEAK_GBPS}
-    rec = K // 2 + K // 32
-    buf = torch.empty(Mo * rec, dtype=torch.uint8, device=dev)
-    us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec))
-    res["quant_gather_top8_records"] = {"us": us, "compulsory_GB/s": compulsory / us * 1e-3}
-    del qg, sg, buf
-    # the paper's literal weight-gradient kernel: row-blocked MXFP4 -> column-wise FP8
-    # (0.53125 B read + 1.03125 B written per element)
-    xc = torch.empty((K, M), dtype=torch.uint8, device=dev)
-    xcs = torch.empty((K, M // 128), dtype=torch.float32, device=dev)
-    us = timed(lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs))
-    b = M * K * (0.53125 + 1.03125)
-    res["row_to_fp8_col"] = {"us": us, "GB/s": b / us * 1e-3, "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
+    if want("quant_from_bf16"):
+        # the paper's BF16-source row quantizer on the same activations (2 B read + 0.53125 B written per element)
+        xbf = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        for r0 in range(0, M, 8192):
+            xbf[r0:r0 + 8192] = (x8[r0:r0 + 8192].view(torch.float8_e4m3fn).float()
+                                 * s[r0:r0 + 8192].repeat_interleave(128, dim=1)).to(torch.bfloat16)
+        qb = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        sb = torch.empty((M, K // 32), dtype=torch.uint8, device=dev)
+        res["quant_from_bf16"] = entry(timed(lambda: mx.mxfp4_quant_from_bf16(xbf, q=qb, sf=sb)),
+                                       M * K * (2.0 + 0.53125))
+        del xbf, qb, sb
+
+    if want("quant_gather_top8") or want("quant_gather_top8_records"):
+        top_k = 8
+        idx = synth.routing_indices(seed=a.seed, num_tokens=M, top_k=top_k, device=dev)
+        Mo = idx.shape[0]
+        compulsory = M * K * 1.03125 + Mo * 4 + Mo * K * 0.53125
+        if want("quant_gather_top8"):
+            qg = torch.empty((Mo, K // 2), dtype=torch.uint8, device=dev)
+            sg = torch.empty((Mo, K // 32), dtype=torch.uint8, device=dev)
+            us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=qg, sf=sg))
+            logical = Mo * K * BYTES_PER_ELEM["quant"]
+            res["quant_gather_top8"] = {"us": us, "logical_GB/s": logical / us * 1e-3,
+                                        "compulsory_GB/s": compulsory / us * 1e-3,
+                                        "frac_of_hbm_peak_compulsory": compulsory / us * 1e-3 / HBM_PEAK_GBPS}
+            del qg, sg
+        if want("quant_gather_top8_records"):
+            rec = K // 2 + K // 32
+            buf = torch.empty(Mo * rec, dtype=torch.uint8, device=dev)
+            us = timed(lambda: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=buf, sf=buf[K // 2:],
+                                                       ld_q=rec, ld_sf=rec))
+            res["quant_gather_top8_records"] = {"us": us, "compulsory_GB/s": compulsory / us * 1e-3}
+            del buf
+
     off, _ = synth.expert_offsets(seed=a.seed, num_experts=32, total_tokens=M - 32 * 128, pad_to=128)
     Mt = int(off[-1])
-    if Mt <= M:
-        offd = off.to(dev)
-        us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mt], sf[:Mt], offd, x_col=xc.view(-1)[:Mt * K],
-                                                           x_col_scale=xcs.view(-1)[:Mt * K // 128]))
-        b = Mt * K * (0.53125 + 1.03125)
-        res["row_to_fp8_col_grouped_32_experts"] = {"rows": Mt, "us": us, "GB/s": b / us * 1e-3,
-                                                    "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
-    del xc, xcs
-    if Mt <= M:
+    offd = off.to(dev)
+    f8 = 0.53125 + 1.03125  # row-blocked MXFP4 read, FP8 + FP32 per 128 written
+    if want("row_to_fp8_col") or want("row_to_fp8_col_grouped_32_experts"):
+        # the paper's literal weight-gradient kernel: row-blocked MXFP4 -> column-wise FP8
+        xc = torch.empty((K, M), dtype=torch.uint8, device=dev)
+        xcs = torch.empty((K, M // 128), dtype=torch.float32, device=dev)
+        if want("row_to_fp8_col"):
+            res["row_to_fp8_col"] = entry(timed(lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs)),
+                                          M * K * f8)
+        if want("row_to_fp8_col_grouped_32_experts") and Mt <= M:
+            us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mt], sf[:Mt], offd, x_col=xc.view(-1)[:Mt * K],
+                                                               x_col_scale=xcs.view(-1)[:Mt * K // 128]))
+            res["row_to_fp8_col_grouped_32_experts"] = entry(us, Mt * K * f8, rows=Mt)
+        del xc, xcs
+    if want("row_to_col_grouped_32_experts") and Mt <= M:
         qc = torch.empty(Mt * K // 2, dtype=torch.uint8, device=dev)
         scc = torch.empty(Mt * K // 32, dtype=torch.uint8, device=dev)
         us = timed(lambda: mx.mxfp4_row_to_col_grouped(q[:Mt], sf[:Mt], offd, q_col=qc, sf_col=scc))
-        b = Mt * K * BYTES_PER_ELEM["row_to_col"]
-        res["row_to_col_grouped_32_experts"] = {"rows": Mt, "us": us, "GB/s": b / us * 1e-3,
-                                                "frac_of_hbm_peak": b / us * 1e-3 / HBM_PEAK_GBPS}
+        res["row_to_col_grouped_32_experts"] = entry(us, Mt * K * BYTES_PER_ELEM["row_to_col"], rows=Mt)
     return res
 
 
