@@ -339,41 +339,37 @@ int mxfp4_ref_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M,
 /* ---------------------------------------------------------------- row-blocked MXFP4 -> column-wise FP8 */
 
 /* Row-blocked MXFP4 (nibbles [M,K/2], 1x32 scales [M,K/32]) -> the transposed matrix as FP8:
- * E4M3 [K,M] plus one FP32 scale per 128 consecutive m at fixed k, [K,M/128] (the layout the
+ * E4M3 [K,M] plus one FP32 scale per 128 consecutive m at fixed k, [K,ceil(M/128)] (the layout the
  * weight-gradient GEMM reads; section 3.4's fused de-quantization + transposition +
  * re-quantization, with the FP4 -> FP8 step of section 3.3 / Algorithm 1 taken along m).
- * For output row k and the 128 rows m of group g, with b_m = sf_row[m][k/32]:
+ * For output row k and the rows m of group g (128 of them; fewer in a last, partial group of a
+ * ragged split), with b_m = sf_row[m][k/32]:
  *   scale[k][g] = 2^(max_m(b_m) - 6 - 127)                       (Algorithm 1 step 1)
  *   x[k][m]     = e2m1(code[m][k]) * 2^(6 - (max(b) - b_m)) rounded to nearest-even E4M3
- * exactly as in mxfp4_ref_dequant_to_fp8, the aligned "blocks" now being the 128 single
- * elements of the column.  A NaN scale byte makes the scale NaN and that row's element 0x7F;
- * the other rows align to the maximum of the non-NaN bytes.  M % 128 == 0. */
-int mxfp4_ref_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
-                             uint8_t *x_col, float *x_col_scale)
+ * exactly as in mxfp4_ref_dequant_to_fp8, the aligned "blocks" now being the single elements
+ * of the column.  A NaN scale byte makes the scale NaN and that row's element 0x7F; the other
+ * rows align to the maximum of the non-NaN bytes. */
+static void fp8_col_of_rows(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                            uint8_t *x_col, float *x_col_scale)
 {
-    if (M < 0 || K < 0 || K % 128 != 0 || M % 128 != 0)
-        return -1;
-    if (M == 0 || K == 0)
-        return 0;
-    if (!q_row || !sf_row || !x_col || !x_col_scale)
-        return -1;
-
+    const int64_t G = (M + 127) / 128;
     double grid[0x7F];
     for (unsigned c = 0; c <= 0x7Eu; ++c)
         grid[c] = e4m3_magnitude(c);
 
     for (int64_t k = 0; k < K; ++k) {
-        for (int64_t g = 0; g < M / 128; ++g) {
+        for (int64_t g = 0; g < G; ++g) {
+            const int n = (int)(M - g * 128 < 128 ? M - g * 128 : 128); /* rows in this group */
             int bmax = 0, any_nan = 0;
-            for (int e = 0; e < 128; ++e) {
+            for (int e = 0; e < n; ++e) {
                 unsigned b = sf_row[(g * 128 + e) * (K / 32) + k / 32];
                 if (b == 0xFFu)
                     any_nan = 1;
                 else if ((int)b > bmax)
                     bmax = (int)b;
             }
-            x_col_scale[k * (M / 128) + g] = any_nan ? (float)NAN : (float)ldexp(1.0, bmax - 6 - 127);
-            for (int e = 0; e < 128; ++e) {
+            x_col_scale[k * G + g] = any_nan ? (float)NAN : (float)ldexp(1.0, bmax - 6 - 127);
+            for (int e = 0; e < n; ++e) {
                 int64_t m = g * 128 + e;
                 unsigned b = sf_row[m * (K / 32) + k / 32];
                 unsigned byte = q_row[m * (K / 2) + k / 2];
@@ -389,6 +385,19 @@ int mxfp4_ref_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_
             }
         }
     }
+}
+
+/* The flat conversion: M % 128 == 0, scales [K, M/128]. */
+int mxfp4_ref_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                             uint8_t *x_col, float *x_col_scale)
+{
+    if (M < 0 || K < 0 || K % 128 != 0 || M % 128 != 0)
+        return -1;
+    if (M == 0 || K == 0)
+        return 0;
+    if (!q_row || !sf_row || !x_col || !x_col_scale)
+        return -1;
+    fp8_col_of_rows(q_row, sf_row, M, K, x_col, x_col_scale);
     return 0;
 }
 
@@ -444,24 +453,32 @@ int mxfp4_ref_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
     return 0;
 }
 
-/* Expert e's FP8 output is its own dense [K, T_e] and [K, T_e/128] matrices, stored back to
- * back at element offsets K*off_e and K*off_e/128.  Every T_e % 128 == 0. */
+/* Ragged splits without padding (section 3.4): any T_e >= 0.  Expert e's FP8 output is its own
+ * dense [K, T_e] matrix at element offset K*off_e, and its scales are its own dense
+ * [K, ceil(T_e/128)] matrix at element offset K * sum_{j<e} ceil(T_j/128); a last group of fewer
+ * than 128 rows takes its maximum over the rows it has.  With every T_e a multiple of 128 the
+ * scale offset is K*off_e/128. */
 int mxfp4_ref_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
                                      const int32_t *expert_offsets, int32_t num_experts,
                                      int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale)
 {
-    if (!offsets_ok(expert_offsets, num_experts, M_total) || K < 0 || K % 128 != 0)
+    if (num_experts <= 0 || !expert_offsets || expert_offsets[0] != 0 ||
+        (int64_t)expert_offsets[num_experts] != M_total || K < 0 || K % 128 != 0)
         return -1;
+    for (int32_t e = 0; e < num_experts; ++e)
+        if (expert_offsets[e + 1] < expert_offsets[e])
+            return -1;
+    if (M_total == 0 || K == 0)
+        return 0;
+    if (!q_row || !sf_row || !x_col || !x_col_scale)
+        return -1;
+    int64_t groups_before = 0;
     for (int32_t e = 0; e < num_experts; ++e) {
         int64_t o = expert_offsets[e], T = expert_offsets[e + 1] - o;
-        if (T % 128 != 0)
-            return -1;
-        int rc = mxfp4_ref_row_to_fp8_col(q_row ? q_row + o * (K / 2) : q_row,
-                                          sf_row ? sf_row + o * (K / 32) : sf_row, T, K,
-                                          x_col ? x_col + o * K : x_col,
-                                          x_col_scale ? x_col_scale + o * K / 128 : x_col_scale);
-        if (rc)
-            return rc;
+        if (T > 0)
+            fp8_col_of_rows(q_row + o * (K / 2), sf_row + o * (K / 32), T, K, x_col + o * K,
+                            x_col_scale + groups_before * K);
+        groups_before += (T + 127) / 128;
     }
     return 0;
 }

@@ -136,13 +136,15 @@ def row_to_fp8_col(q_row, sf_row):
 
 
 def row_to_fp8_col_grouped(q_row, sf_row, expert_offsets):
-    """Flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,T_e/128] at K*off_e/128."""
+    """Flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,ceil(T_e/128)] at K*sum_{j<e} ceil(T_j/128).
+    Any T_e >= 0 (ragged splits without padding)."""
     q_row = _c(q_row, np.uint8)
     sf_row = _c(sf_row, np.uint8)
     off = _c(expert_offsets, np.int32)
     M, K = q_row.shape[0], q_row.shape[1] * 2
+    groups = int(((np.diff(off.astype(np.int64)) + 127) // 128).sum())
     xc = np.empty(M * K, np.uint8)
-    xs = np.empty(M * K // 128, np.float32)
+    xs = np.empty(groups * K, np.float32)
     rc = lib().mxfp4_ref_row_to_fp8_col_grouped(_p(q_row, _u8p), _p(sf_row, _u8p), _p(off, _i32p),
                                                 off.shape[0] - 1, M, K, _p(xc, _u8p), _p(xs, _f32p))
     _check(rc, "row_to_fp8_col_grouped")

@@ -152,8 +152,46 @@ def test_grouped_equals_flat_per_expert():
         wx, ws = ref.row_to_fp8_col(q[lo:hi], sf[lo:hi])
         assert (xc[K * lo:K * hi].reshape(K, hi - lo) == wx).all()
         assert (xs[K * lo // 128:K * hi // 128].reshape(K, (hi - lo) // 128).view(np.uint32) == ws.view(np.uint32)).all()
-    try:
-        ref.row_to_fp8_col_grouped(q, sf, np.array([0, 96, 640], np.int32))
-        assert False, "T_e % 128 != 0 must be rejected"
-    except ValueError:
-        pass
+
+
+def test_ragged_splits_without_padding():
+    # any T_e: expert e's bytes at K*off_e, its scales [K, ceil(T_e/128)] after those of the experts before
+    K = 256
+    off = np.array([0, 5, 5, 133, 389, 420, 676, 677], np.int32)          # T = 5 0 128 256 31 256 1
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=21, scale_center=118, scale_spread=9)
+    q, sf = q.numpy(), sf.numpy()
+    sf[130, :] = 140                                                       # a maximum near a group edge
+    sf[419, 2] = 0xFF                                                      # NaN in a partial group
+    xc, xs = ref.row_to_fp8_col_grouped(q, sf, off)
+    groups = [(int(off[e + 1] - off[e]) + 127) // 128 for e in range(len(off) - 1)]
+    assert xs.shape[0] == K * sum(groups) and xc.shape[0] == K * M
+    gb = 0
+    nib = unpack_nibbles(q)
+    for e in range(len(off) - 1):
+        lo, hi = int(off[e]), int(off[e + 1])
+        T, G = hi - lo, groups[e]
+        if T == 0:
+            continue
+        got_x = xc[K * lo:K * hi].reshape(K, T)
+        got_s = xs[K * gb:K * (gb + G)].reshape(K, G)
+        # (a) the same rows padded with zero rows (scale byte 0) to a multiple of 128, through the flat function
+        pad = G * 128 - T
+        qp = np.concatenate([q[lo:hi], np.zeros((pad, K // 2), np.uint8)])
+        sp = np.concatenate([sf[lo:hi], np.zeros((pad, K // 32), np.uint8)])
+        wx, ws = ref.row_to_fp8_col(qp, sp)
+        assert (got_x == wx[:, :T]).all(), e
+        assert (got_s.view(np.uint32) == ws.view(np.uint32)).all(), e
+        # (b) exact rationals on the partial last group of a few columns
+        n_last = T - (G - 1) * 128
+        for k in (0, 37, 70, K - 1):
+            rows = slice(lo + (G - 1) * 128, hi)
+            bytes_ = [int(b) for b in sf[rows, k // 32]]
+            if 0xFF in bytes_:
+                assert np.isnan(got_s[k, G - 1])
+                continue
+            S, want = bf.row_to_fp8_col_column([int(n) for n in nib[rows, k]], bytes_)
+            assert Fraction(float(got_s[k, G - 1])) == S
+            assert got_x[k, (G - 1) * 128:].tolist() == want and len(want) == n_last
+        gb += G
+    assert np.isnan(xs[K * (groups[0] + groups[1] + groups[2] + groups[3]) + 64 * groups[4]])   # k = 64, expert 4
