@@ -238,7 +238,7 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
     Mt = int(off[-1])
     offd = off.to(dev)
     f8 = 0.53125 + 1.03125  # row-blocked MXFP4 read, FP8 + FP32 per 128 written
-    if want("row_to_fp8_col") or want("row_to_fp8_col_grouped_32_experts"):
+    if want("row_to_fp8_col") or want("row_to_fp8_col_grouped_32_experts") or want("row_to_fp8_col_ragged_32_experts"):
         # the paper's literal weight-gradient kernel: row-blocked MXFP4 -> column-wise FP8
         xc = torch.empty((K, M), dtype=torch.uint8, device=dev)
         xcs = torch.empty((K, M // 128), dtype=torch.float32, device=dev)
@@ -249,6 +249,14 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
             us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mt], sf[:Mt], offd, x_col=xc.view(-1)[:Mt * K],
                                                                x_col_scale=xcs.view(-1)[:Mt * K // 128]))
             res["row_to_fp8_col_grouped_32_experts"] = entry(us, Mt * K * f8, rows=Mt)
+        if want("row_to_fp8_col_ragged_32_experts"):
+            # the same expert counts without padding: arbitrary T_e, unaligned rows, partial last groups
+            offr, _ = synth.expert_offsets(seed=a.seed, num_experts=32, total_tokens=M - 32 * 128, pad_to=1)
+            Mr = int(offr[-1])
+            offrd = offr.to(dev)
+            us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mr], sf[:Mr], offrd, x_col=xc.view(-1)[:Mr * K],
+                                                               x_col_scale=xcs.view(-1)))
+            res["row_to_fp8_col_ragged_32_experts"] = entry(us, Mr * K * f8, rows=Mr)
         del xc, xcs
     if want("row_to_col_grouped_32_experts") and Mt <= M:
         qc = torch.empty(Mt * K // 2, dtype=torch.uint8, device=dev)

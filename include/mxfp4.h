@@ -138,9 +138,15 @@ mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_ro
 mxfp4_status mxfp4_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
                                   uint8_t *x_col, float *x_col_scale, void *hip_stream);
 
-/* The same per expert (expert_offsets as above, every T_e a multiple of 128): expert e's output is
- * its own dense [K, T_e] and [K, T_e/128] matrices at element offsets K*off_e of x_col and
- * K*off_e/128 of x_col_scale.  No scale group crosses an expert boundary. */
+/* The same per expert, for ragged splits without padding (paper sec. 3.4): expert_offsets as above
+ * but every T_e may be ANY length >= 0, and M_total need not be a multiple of 128.
+ *   x_col        expert e's own dense [K, T_e] matrix at element offset K*off_e: contiguous storage
+ *                without padding (rows of T_e bytes, so vector stores are unaligned when T_e % 16 != 0)
+ *   x_col_scale  expert e's own dense [K, ceil(T_e/128)] matrix at element offset
+ *                K * sum_{j<e} ceil(T_j/128) (= K*off_e/128 when every T_e is a multiple of 128);
+ *                the buffer holds K * sum_e ceil(T_e/128) <= K * (M_total/128 + num_experts) floats.
+ *                A last group of fewer than 128 rows takes its maximum over the rows it has.
+ * No scale group crosses an expert boundary. */
 mxfp4_status mxfp4_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
                                           const int32_t *expert_offsets, int32_t num_experts,
                                           int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale,

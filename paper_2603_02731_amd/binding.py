@@ -196,7 +196,9 @@ def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=Non
 
 
 def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_col_scale=None, stream=None):
-    """Outputs are flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,T_e/128] at K*off_e/128."""
+    """Outputs are flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,ceil(T_e/128)] at
+    K*sum_{j<e} ceil(T_j/128); any T_e.  A scale buffer allocated here has the upper-bound size
+    K*(M//128 + num_experts)."""
     _dev(q_row, torch.uint8, "q_row")
     _dev(sf_row, torch.uint8, "sf_row")
     _dev(expert_offsets, torch.int32, "expert_offsets")
@@ -204,7 +206,8 @@ def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_co
     if x_col is None:
         x_col = torch.empty(M * K, dtype=torch.uint8, device=q_row.device)
     if x_col_scale is None:
-        x_col_scale = torch.empty(M * K // 128, dtype=torch.float32, device=q_row.device)
+        x_col_scale = torch.empty(K * (M // 128 + expert_offsets.shape[0] - 1), dtype=torch.float32,
+                                  device=q_row.device)
     st = lib().mxfp4_row_to_fp8_col_grouped(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(),
                                             expert_offsets.shape[0] - 1, M, K, x_col.data_ptr(),
                                             x_col_scale.data_ptr(), _stream(stream))

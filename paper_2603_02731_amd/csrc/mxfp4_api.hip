@@ -127,7 +127,8 @@ static mxfp4_status row_to_fp8_col_common(const uint8_t *q_row, const uint8_t *s
                                           const int32_t *expert_offsets, int32_t num_experts, int64_t M,
                                           int64_t K, uint8_t *x_col, float *x_col_scale, void *hip_stream)
 {
-    if (M < 0 || K < 0 || K % 128 != 0 || M % 128 != 0)
+    // the flat form has whole scale groups; the splits of the grouped form may have any length
+    if (M < 0 || K < 0 || K % 128 != 0 || (!expert_offsets && M % 128 != 0))
         return MXFP4_ERR_SHAPE;
     if (M == 0 || K == 0)
         return MXFP4_OK;

@@ -24,6 +24,11 @@ namespace mxfp4 {
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The same through pointers of any alignment (global memory takes unaligned vector accesses).
+typedef u32x4 __attribute__((aligned(1))) u32x4_unaligned;
+typedef uint64_t __attribute__((aligned(1))) u64_unaligned;
+typedef uint32_t __attribute__((aligned(1))) u32_unaligned;
+typedef uint16_t __attribute__((aligned(1))) u16_unaligned;
 
 __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -121,13 +126,16 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
 // (expert e contributes ceil(T_e / TILE_ROWS) tiles, T_e = off[e+1] - off[e]).  Uniform per
 // workgroup; every wave evaluates it on its own, 64 experts at a time: one coalesced load of the
 // offsets, a wave prefix sum of the tile counts and a ballot, instead of a serial scan whose
-// every step waits for memory.  On success `tile` becomes the tile index inside the expert.
-template <uint32_t TILE_ROWS>
+// every step waits for memory.  On success `tile` becomes the tile index inside the expert, and
+// with UNIT_ROWS != 0 `units_before` the sum of ceil(T_j / UNIT_ROWS) over the experts before
+// it (where its scale groups start when the splits are not padded).
+template <uint32_t TILE_ROWS, uint32_t UNIT_ROWS = 0>
 __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_experts, uint32_t *tile,
-                                               uint32_t *row_base, uint32_t *rows)
+                                               uint32_t *row_base, uint32_t *rows,
+                                               uint32_t *units_before = nullptr)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    uint32_t before = 0; // tiles of the experts in earlier chunks
+    uint32_t before = 0, ubefore = 0; // tiles / units of the experts in earlier chunks
     for (int32_t base = 0; base < num_experts; base += 64) {
         const int32_t e = base + (int32_t)lane;
         uint32_t lo = 0, hi = 0;
@@ -136,11 +144,16 @@ __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_e
             hi = (uint32_t)off[e + 1];
         }
         const uint32_t nt = (hi - lo + TILE_ROWS - 1u) / TILE_ROWS;
-        uint32_t incl = nt; // inclusive prefix sum over the wave
+        const uint32_t nu = UNIT_ROWS ? (hi - lo + UNIT_ROWS - 1u) / (UNIT_ROWS ? UNIT_ROWS : 1u) : 0u;
+        uint32_t incl = nt, uincl = nu; // inclusive prefix sums over the wave
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
             incl += lane >= (uint32_t)d ? up : 0u;
+            if (UNIT_ROWS) {
+                const uint32_t uup = (uint32_t)__shfl_up((int)uincl, d, 64);
+                uincl += lane >= (uint32_t)d ? uup : 0u;
+            }
         }
         const uint64_t hit = __ballot(before + incl > *tile);
         if (hit != 0ull) {
@@ -149,9 +162,13 @@ __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_e
             *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo, l);
             *rows = (uint32_t)__builtin_amdgcn_readlane((int)(hi - lo), l);
             *tile -= before + excl;
+            if (UNIT_ROWS)
+                *units_before = ubefore + (uint32_t)__builtin_amdgcn_readlane((int)(uincl - nu), l);
             return true;
         }
         before += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        if (UNIT_ROWS)
+            ubefore += (uint32_t)__builtin_amdgcn_readlane((int)uincl, 63);
     }
     return false;
 }

@@ -95,6 +95,25 @@ __device__ __forceinline__ uint32_t max_of_8_bytes(const uint8_t *p)
     return max(t, u);
 }
 
+// The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.
+__device__ __forceinline__ void store_head_bytes(uint8_t *dst, const u32x4 v, uint32_t n)
+{
+    uint32_t pos = 0; // bytes done
+    if (n & 8u) {
+        *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)v.y << 32) | v.x;
+        pos = 8;
+    }
+    if (n & 4u) {
+        *reinterpret_cast<u32_unaligned *>(dst + pos) = pos ? v.z : v.x;
+        pos += 4;
+    }
+    const uint32_t d = pos == 0u ? v.x : pos == 4u ? v.y : pos == 8u ? v.z : v.w; // the dword still open
+    if (n & 2u)
+        *reinterpret_cast<u16_unaligned *>(dst + pos) = (uint16_t)d;
+    if (n & 1u)
+        dst[pos + (n & 2u)] = (uint8_t)(d >> (8u * (n & 2u)));
+}
+
 } // namespace fp8col
 
 using namespace fp8col;
@@ -110,23 +129,25 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k))
         return;
 
-    // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
-    uint32_t row_base = 0, rows = a.M;
-    if (a.expert_offsets && !tile_of_expert<TILE_M>(a.expert_offsets, a.num_experts, &tile_m, &row_base, &rows))
+    // ---- which rows: the whole matrix, or one expert's slice of any length (uniform per workgroup)
+    uint32_t row_base = 0, rows = a.M, groups_before = 0;
+    if (a.expert_offsets &&
+        !tile_of_expert<TILE_M, 128>(a.expert_offsets, a.num_experts, &tile_m, &row_base, &rows, &groups_before))
         return;
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
     if (m0 >= rows)
         return;
-    const uint32_t n_rows = min((uint32_t)TILE_M, rows - m0) & ~127u; // rows present: 128 or 256
-    const uint32_t n_g = n_rows / 128u;                               // 128-row scale groups present
+    const uint32_t n_rows = min((uint32_t)TILE_M, rows - m0); // rows present: 1..256
+    const uint32_t n_g = (n_rows + 127u) / 128u;              // scale groups present, the last maybe partial
     const uint32_t k0 = tile_k * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
 
-    // expert e's output is its own dense [K, rows] and [K, rows/128]
+    // expert e's output is its own dense [K, rows] and [K, ceil(rows/128)], the latter after the
+    // scale groups of the experts before it
     uint8_t *out_x = a.x_col + (size_t)a.K * row_base;
-    float *out_s = a.x_col_scale + (size_t)a.K * row_base / 128u;
-    const size_t pitch_x = rows, pitch_s = rows / 128u;
+    float *out_s = a.x_col_scale + (size_t)a.K * (a.expert_offsets ? groups_before : 0u);
+    const size_t pitch_x = rows, pitch_s = (rows + 127u) / 128u;
 
     const uint32_t tid = threadIdx.x;
     const uint32_t rgl = tid >> 5, cg = tid & 31u;
@@ -139,10 +160,20 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     if (active) {
         const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
         const uint32_t lane_off = rgl * RPL * pitch + cg * 4u; // < 2^32: K is at most 2^24
+        if (n_rows == (uint32_t)TILE_M) {
 #pragma unroll
-        for (int i = 0; i < RPL; ++i)
-            w[i] = __builtin_nontemporal_load(
-                reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+            for (int i = 0; i < RPL; ++i)
+                w[i] = __builtin_nontemporal_load(
+                    reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+        } else {
+            // ragged end of a split: rows past it are read from its last row instead (their
+            // results are never stored and their scale bytes are staged as 0)
+            const uint32_t last = n_rows - 1u - rgl * RPL;
+#pragma unroll
+            for (int i = 0; i < RPL; ++i)
+                w[i] = __builtin_nontemporal_load(
+                    reinterpret_cast<const uint32_t *>(tile_src + lane_off + min((uint32_t)i, last) * pitch));
+        }
     }
 
     // ---- stage the tile's row scales (PARTS threads per row, KBT bytes each) and reduce them:
@@ -301,17 +332,30 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
             const uint32_t lslot = (pslot - (tid >> 4)) & 15u; // 16 bytes = rows 16*lslot.. of the tile
             const uint32_t lane_off = (tid >> 4) * 8u * (uint32_t)pitch_x + lslot * 16u;
             uint8_t *krow0 = out_x + (size_t)(k0 + ph * CP) * pitch_x + m0;
+            // bytes of this lane's 16-byte piece that exist: 16, or fewer at the ragged end of a split
+            const uint32_t have = lslot * 16u < n_rows ? min(16u, n_rows - lslot * 16u) : 0u;
             static_for<HALVES>([&](auto oddp) {
                 constexpr int odd = decltype(oddp)::value;
-                if ((odd * 16u + (tid >> 4)) * 8u < cols && lslot * 16u < n_rows) {
+                if ((odd * 16u + (tid >> 4)) * 8u < cols && have != 0u) {
+                    if (have == 16u) {
 #pragma unroll
-                    for (int c = 0; c < CP; ++c) {
-                        u32x4 *dst = reinterpret_cast<u32x4 *>(krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off);
+                        for (int c = 0; c < CP; ++c) {
+                            uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
+                            const u32x4 v = s_out[(HALVES * c + odd) * T_THREADS + tid];
+                            // the address is 16-byte aligned unless the splits are ragged
 #if MXFP4_F8C_NT
-                        __builtin_nontemporal_store(s_out[(HALVES * c + odd) * T_THREADS + tid], dst);
+                            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_unaligned *>(dst));
 #else
-                        *dst = s_out[(HALVES * c + odd) * T_THREADS + tid];
+                            *reinterpret_cast<u32x4_unaligned *>(dst) = v;
 #endif
+                        }
+                    } else {
+#pragma nounroll
+                        for (int c = 0; c < CP; ++c) {
+                            uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
+                            const u32x4 v = s_out[(HALVES * c + odd) * T_THREADS + tid];
+                            store_head_bytes(dst, v, have);
+                        }
                     }
                 }
             });

@@ -343,13 +343,13 @@ def test_row_to_fp8_col_grouped():
     q, sf = q.numpy(), sf.numpy()
     x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), off.to(DEV))
     wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off.numpy())
-    assert_same(host(xs), wxs, "grouped row->FP8 col: group scales")
+    assert_same(host(xs)[:wxs.size], wxs, "grouped row->FP8 col: group scales")
     assert_same(host(x), wx, "grouped row->FP8 col: E4M3 bytes")
     # one expert holding everything equals the flat call
     one = torch.tensor([0, 1152], dtype=torch.int32)
     x1, xs1 = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), one.to(DEV))
     fx, fxs = ref.row_to_fp8_col(q, sf)
-    assert_same(host(xs1).reshape(fxs.shape), fxs, "single expert: group scales")
+    assert_same(host(xs1)[:fxs.size].reshape(fxs.shape), fxs, "single expert: group scales")
     assert_same(host(x1).reshape(fx.shape), fx, "single expert: E4M3 bytes")
 
 
@@ -388,5 +388,27 @@ def test_grouped_more_experts_than_a_wave():
     assert_same(host(qc), wqc, "150 experts row->col nibbles")
     x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd)
     wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off)
-    assert_same(host(xs), wxs, "150 experts row->FP8 col scales")
+    assert_same(host(xs)[:wxs.size], wxs, "150 experts row->FP8 col scales")
     assert_same(host(x), wx, "150 experts row->FP8 col bytes")
+
+
+@pytest.mark.parametrize("K", [256, 384])
+def test_row_to_fp8_col_ragged_splits_without_padding(K):
+    # any T_e: partial last scale groups, partial tiles, unaligned rows; outputs are checked together
+    # with guard bytes around them
+    T = [5, 0, 128, 256, 31, 257, 1, 300, 16, 15, 17, 511, 0, 130]
+    off = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=31 + K, scale_center=118, scale_spread=9, nan_scale_frac=0.002)
+    q, sf = q.numpy(), sf.numpy()
+    wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off)
+    guard = 4096
+    xbuf = torch.full((guard + wx.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    sbuf = torch.full((guard + wxs.size + guard,), -7.0, dtype=torch.float32, device=DEV)
+    mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV),
+                                    x_col=xbuf[guard:guard + wx.size], x_col_scale=sbuf[guard:guard + wxs.size])
+    xb, sb = host(xbuf), host(sbuf)
+    assert (xb[:guard] == 0xA5).all() and (xb[guard + wx.size:] == 0xA5).all(), "bytes written outside x_col"
+    assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
+    assert_same(sb[guard:guard + wxs.size], wxs, "ragged row->FP8 col: group scales")
+    assert_same(xb[guard:guard + wx.size], wx, "ragged row->FP8 col: E4M3 bytes")
