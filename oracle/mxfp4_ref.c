@@ -349,8 +349,14 @@ int mxfp4_ref_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M,
  * exactly as in mxfp4_ref_dequant_to_fp8, the aligned "blocks" now being the single elements
  * of the column.  A NaN scale byte makes the scale NaN and that row's element 0x7F; the other
  * rows align to the maximum of the non-NaN bytes. */
+#define FP8_COL_ALIGN 0   /* Algorithm 1's scale alignment along m */
+#define FP8_COL_REQUANT 1 /* re-quantization from the group's maximum, see below */
+
+static void fp8_col_requant_group(const uint8_t *q_row, const uint8_t *sf_row, int64_t K, int64_t k, int64_t m0,
+                                  int n, const double *grid, uint8_t *x_row, float *scale);
+
 static void fp8_col_of_rows(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
-                            uint8_t *x_col, float *x_col_scale)
+                            uint8_t *x_col, float *x_col_scale, int rule)
 {
     const int64_t G = (M + 127) / 128;
     double grid[0x7F];
@@ -360,6 +366,11 @@ static void fp8_col_of_rows(const uint8_t *q_row, const uint8_t *sf_row, int64_t
     for (int64_t k = 0; k < K; ++k) {
         for (int64_t g = 0; g < G; ++g) {
             const int n = (int)(M - g * 128 < 128 ? M - g * 128 : 128); /* rows in this group */
+            if (rule == FP8_COL_REQUANT) {
+                fp8_col_requant_group(q_row, sf_row, K, k, g * 128, n, grid, x_col + k * M + g * 128,
+                                      &x_col_scale[k * G + g]);
+                continue;
+            }
             int bmax = 0, any_nan = 0;
             for (int e = 0; e < n; ++e) {
                 unsigned b = sf_row[(g * 128 + e) * (K / 32) + k / 32];
@@ -387,6 +398,53 @@ static void fp8_col_of_rows(const uint8_t *q_row, const uint8_t *sf_row, int64_t
     }
 }
 
+/* The other reading of the fused kernel (section 3.4: "de-quantization, transposition and
+ * re-quantization", with the power-of-two scale 2^ceil(log2 x) of its bit-level arithmetic item):
+ * the n elements of one output row k and one group take their exact values
+ * v_m = +-e2m1(code) * 2^(b_m - 127); the group scale is the smallest power of two S with
+ * max|v| / S <= 448 (the largest E4M3 magnitude), 1.0 for an all-zero group; every element is
+ * v_m / S rounded to nearest-even E4M3 (gradual underflow; no saturation can occur).
+ * A NaN scale byte makes the scale NaN and its row's element 0x7F; the maximum is taken over the
+ * other rows. */
+static void fp8_col_requant_group(const uint8_t *q_row, const uint8_t *sf_row, int64_t K, int64_t k, int64_t m0,
+                                  int n, const double *grid, uint8_t *x_row, float *scale)
+{
+    double amax = 0.0;
+    int any_nan = 0;
+    for (int e = 0; e < n; ++e) {
+        unsigned b = sf_row[(m0 + e) * (K / 32) + k / 32];
+        unsigned byte = q_row[(m0 + e) * (K / 2) + k / 2];
+        unsigned nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
+        if (b == 0xFFu) {
+            any_nan = 1;
+            continue;
+        }
+        double a = ldexp(e2m1_magnitude(nib & 7u), (int)b - 127);
+        if (a > amax)
+            amax = a;
+    }
+    int j = 0; /* S = 2^j */
+    if (amax > 0.0) {
+        int ex;
+        frexp(amax, &ex);
+        j = ex - 12;                    /* 448 * 2^(ex-12) < 2^(ex-1) <= amax: too small, step up */
+        while (amax > ldexp(448.0, j))  /* exact comparisons: both sides are doubles without rounding */
+            ++j;
+    }
+    *scale = any_nan ? (float)NAN : (float)ldexp(1.0, j);
+    for (int e = 0; e < n; ++e) {
+        unsigned b = sf_row[(m0 + e) * (K / 32) + k / 32];
+        unsigned byte = q_row[(m0 + e) * (K / 2) + k / 2];
+        unsigned nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
+        if (b == 0xFFu) {
+            x_row[e] = 0x7Fu;
+            continue;
+        }
+        double r = ldexp(e2m1_magnitude(nib & 7u), (int)b - 127 - j);
+        x_row[e] = (uint8_t)(((nib >> 3) << 7) | e4m3_round_nearest_even(r, grid));
+    }
+}
+
 /* The flat conversion: M % 128 == 0, scales [K, M/128]. */
 int mxfp4_ref_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
                              uint8_t *x_col, float *x_col_scale)
@@ -397,7 +455,20 @@ int mxfp4_ref_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_
         return 0;
     if (!q_row || !sf_row || !x_col || !x_col_scale)
         return -1;
-    fp8_col_of_rows(q_row, sf_row, M, K, x_col, x_col_scale);
+    fp8_col_of_rows(q_row, sf_row, M, K, x_col, x_col_scale, FP8_COL_ALIGN);
+    return 0;
+}
+
+int mxfp4_ref_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                                     uint8_t *x_col, float *x_col_scale)
+{
+    if (M < 0 || K < 0 || K % 128 != 0 || M % 128 != 0)
+        return -1;
+    if (M == 0 || K == 0)
+        return 0;
+    if (!q_row || !sf_row || !x_col || !x_col_scale)
+        return -1;
+    fp8_col_of_rows(q_row, sf_row, M, K, x_col, x_col_scale, FP8_COL_REQUANT);
     return 0;
 }
 
@@ -458,9 +529,9 @@ int mxfp4_ref_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
  * [K, ceil(T_e/128)] matrix at element offset K * sum_{j<e} ceil(T_j/128); a last group of fewer
  * than 128 rows takes its maximum over the rows it has.  With every T_e a multiple of 128 the
  * scale offset is K*off_e/128. */
-int mxfp4_ref_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
-                                     const int32_t *expert_offsets, int32_t num_experts,
-                                     int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale)
+static int fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                           int32_t num_experts, int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale,
+                           int rule)
 {
     if (num_experts <= 0 || !expert_offsets || expert_offsets[0] != 0 ||
         (int64_t)expert_offsets[num_experts] != M_total || K < 0 || K % 128 != 0)
@@ -477,10 +548,26 @@ int mxfp4_ref_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row
         int64_t o = expert_offsets[e], T = expert_offsets[e + 1] - o;
         if (T > 0)
             fp8_col_of_rows(q_row + o * (K / 2), sf_row + o * (K / 32), T, K, x_col + o * K,
-                            x_col_scale + groups_before * K);
+                            x_col_scale + groups_before * K, rule);
         groups_before += (T + 127) / 128;
     }
     return 0;
+}
+
+int mxfp4_ref_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                     const int32_t *expert_offsets, int32_t num_experts,
+                                     int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale)
+{
+    return fp8_col_grouped(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
+                           FP8_COL_ALIGN);
+}
+
+int mxfp4_ref_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                             const int32_t *expert_offsets, int32_t num_experts,
+                                             int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale)
+{
+    return fp8_col_grouped(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
+                           FP8_COL_REQUANT);
 }
 
 /* ---------------------------------------------------------------- scalar entry points for the pins */

@@ -47,9 +47,9 @@ def row_to_col(q, sf, workers=WORKERS):
     return np.concatenate([o[0] for o in outs], axis=1), np.concatenate([o[1] for o in outs], axis=1)
 
 
-def row_to_fp8_col(q, sf, workers=WORKERS):
+def row_to_fp8_col(q, sf, workers=WORKERS, requant=False):
     q, sf = np.ascontiguousarray(q), np.ascontiguousarray(sf)
     rs = _ranges(q.shape[0], 128, workers)
     with ThreadPoolExecutor(workers) as ex:
-        outs = list(ex.map(lambda r: ref.row_to_fp8_col(q[r[0]:r[1]], sf[r[0]:r[1]]), rs))
+        outs = list(ex.map(lambda r: ref.row_to_fp8_col(q[r[0]:r[1]], sf[r[0]:r[1]], requant=requant), rs))
     return np.concatenate([o[0] for o in outs], axis=1), np.concatenate([o[1] for o in outs], axis=1)

@@ -36,6 +36,10 @@ def lib():
         L.mxfp4_ref_row_to_fp8_col.argtypes = [_u8p, _u8p, _i64, _i64, _u8p, _f32p]
         L.mxfp4_ref_row_to_fp8_col_grouped.argtypes = [_u8p, _u8p, _i32p, ctypes.c_int32, _i64, _i64, _u8p, _f32p]
         L.mxfp4_ref_row_to_fp8_col.restype = ctypes.c_int
+        L.mxfp4_ref_row_to_fp8_col_requant.argtypes = L.mxfp4_ref_row_to_fp8_col.argtypes
+        L.mxfp4_ref_row_to_fp8_col_requant_grouped.argtypes = L.mxfp4_ref_row_to_fp8_col_grouped.argtypes
+        L.mxfp4_ref_row_to_fp8_col_requant.restype = ctypes.c_int
+        L.mxfp4_ref_row_to_fp8_col_requant_grouped.restype = ctypes.c_int
         L.mxfp4_ref_row_to_fp8_col_grouped.restype = ctypes.c_int
         for f in (L.mxfp4_ref_quant_from_fp8, L.mxfp4_ref_dequant_to_fp8, L.mxfp4_ref_row_to_col,
                   L.mxfp4_ref_quant_from_fp8_grouped, L.mxfp4_ref_row_to_col_grouped):
@@ -123,19 +127,21 @@ def row_to_col(q_row, sf_row):
     return qc, sc
 
 
-def row_to_fp8_col(q_row, sf_row):
-    """[M,K/2] + [M,K/32] -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128])."""
+def row_to_fp8_col(q_row, sf_row, requant=False):
+    """[M,K/2] + [M,K/32] -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128]).
+    requant=False: Algorithm 1's scale alignment along m; True: re-quantization from the group maximum."""
     q_row = _c(q_row, np.uint8)
     sf_row = _c(sf_row, np.uint8)
     M, K = q_row.shape[0], q_row.shape[1] * 2
     xc = np.empty((K, M), np.uint8)
     xs = np.empty((K, M // 128), np.float32)
-    rc = lib().mxfp4_ref_row_to_fp8_col(_p(q_row, _u8p), _p(sf_row, _u8p), M, K, _p(xc, _u8p), _p(xs, _f32p))
+    fn = lib().mxfp4_ref_row_to_fp8_col_requant if requant else lib().mxfp4_ref_row_to_fp8_col
+    rc = fn(_p(q_row, _u8p), _p(sf_row, _u8p), M, K, _p(xc, _u8p), _p(xs, _f32p))
     _check(rc, "row_to_fp8_col")
     return xc, xs
 
 
-def row_to_fp8_col_grouped(q_row, sf_row, expert_offsets):
+def row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, requant=False):
     """Flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,ceil(T_e/128)] at K*sum_{j<e} ceil(T_j/128).
     Any T_e >= 0 (ragged splits without padding)."""
     q_row = _c(q_row, np.uint8)
@@ -145,8 +151,8 @@ def row_to_fp8_col_grouped(q_row, sf_row, expert_offsets):
     groups = int(((np.diff(off.astype(np.int64)) + 127) // 128).sum())
     xc = np.empty(M * K, np.uint8)
     xs = np.empty(groups * K, np.float32)
-    rc = lib().mxfp4_ref_row_to_fp8_col_grouped(_p(q_row, _u8p), _p(sf_row, _u8p), _p(off, _i32p),
-                                                off.shape[0] - 1, M, K, _p(xc, _u8p), _p(xs, _f32p))
+    fn = lib().mxfp4_ref_row_to_fp8_col_requant_grouped if requant else lib().mxfp4_ref_row_to_fp8_col_grouped
+    rc = fn(_p(q_row, _u8p), _p(sf_row, _u8p), _p(off, _i32p), off.shape[0] - 1, M, K, _p(xc, _u8p), _p(xs, _f32p))
     _check(rc, "row_to_fp8_col_grouped")
     return xc, xs
 

@@ -169,3 +169,20 @@ def row_to_fp8_col_column(nibs, sf_bytes):
         real = E2M1_GRID[n & 7] * pow2(b - 127)
         out.append(((n >> 3) << 7) | nearest_even_code(real / S, E4M3_GRID))
     return S, out
+
+
+def row_to_fp8_col_requant_column(nibs, sf_bytes):
+    """One output column group under the re-quantization reading: the exact values v_m, the smallest power
+    of two S with max|v| <= 448 * S (S = 1 for an all-zero group), and v_m / S to the nearest E4M3 (ties to
+    the even code).  No NaN byte.  Returns (S, [bytes])."""
+    vals = [E2M1_GRID[n & 7] * pow2(b - 127) for n, b in zip(nibs, sf_bytes)]
+    amax = max(vals)
+    if amax == 0:
+        S = Fraction(1)
+    else:
+        j = floor_log2(amax) - 12
+        while 448 * pow2(j) < amax:
+            j += 1
+        assert 448 * pow2(j) >= amax and 448 * pow2(j - 1) < amax
+        S = pow2(j)
+    return S, [((n >> 3) << 7) | nearest_even_code(v / S, E4M3_GRID) for n, v in zip(nibs, vals)]
