@@ -238,13 +238,18 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
     Mt = int(off[-1])
     offd = off.to(dev)
     f8 = 0.53125 + 1.03125  # row-blocked MXFP4 read, FP8 + FP32 per 128 written
-    if want("row_to_fp8_col") or want("row_to_fp8_col_grouped_32_experts") or want("row_to_fp8_col_ragged_32_experts"):
+    if any(want(n) for n in ("row_to_fp8_col", "row_to_fp8_col_requant", "row_to_fp8_col_grouped_32_experts",
+                             "row_to_fp8_col_ragged_32_experts")):
         # the paper's literal weight-gradient kernel: row-blocked MXFP4 -> column-wise FP8
         xc = torch.empty((K, M), dtype=torch.uint8, device=dev)
         xcs = torch.empty((K, M // 128), dtype=torch.float32, device=dev)
         if want("row_to_fp8_col"):
             res["row_to_fp8_col"] = entry(timed(lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs)),
                                           M * K * f8)
+        if want("row_to_fp8_col_requant"):
+            # the other reading: scale from the group maximum (two passes over the nibbles in registers)
+            res["row_to_fp8_col_requant"] = entry(
+                timed(lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs, requant=True)), M * K * f8)
         if want("row_to_fp8_col_grouped_32_experts") and Mt <= M:
             us = timed(lambda: mx.mxfp4_row_to_fp8_col_grouped(q[:Mt], sf[:Mt], offd, x_col=xc.view(-1)[:Mt * K],
                                                                x_col_scale=xcs.view(-1)[:Mt * K // 128]))

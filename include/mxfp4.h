@@ -152,6 +152,23 @@ mxfp4_status mxfp4_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *s
                                           int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale,
                                           void *hip_stream);
 
+/* The same two conversions under the other reading of the paper's fused kernel (sec. 3.4:
+ * de-quantization, transposition and RE-QUANTIZATION, with the power-of-two scale
+ * 2^ceil(log2 x) of its bit-level arithmetic item): every element takes its exact value
+ * v = e2m1(code) * 2^(b_m - 127); per output row k and 128 consecutive m the scale is the smallest
+ * power of two S with max|v| <= 448 * S (1.0 for an all-zero group, an FP32 subnormal below
+ * 2^-126), and x_col[k][m] = E4M3 code of v / S, rounded to nearest-even.  Never a coarser scale
+ * than the alignment form above, and the same bytes whenever the two scales coincide.
+ * Arguments, layouts, limits and the NaN rule are those of mxfp4_row_to_fp8_col and
+ * mxfp4_row_to_fp8_col_grouped (ragged splits of any length included). */
+mxfp4_status mxfp4_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                                          uint8_t *x_col, float *x_col_scale, void *hip_stream);
+
+mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                                  const int32_t *expert_offsets, int32_t num_experts,
+                                                  int64_t M_total, int64_t K, uint8_t *x_col,
+                                                  float *x_col_scale, void *hip_stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp4_status_string(mxfp4_status status);
 

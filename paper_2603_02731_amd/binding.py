@@ -16,7 +16,8 @@ OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_OFFSETS, ERR_LAUNCH = 0, -1, -2, -3, -4,
 
 EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
            "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_row_to_fp8_col",
-           "mxfp4_row_to_fp8_col_grouped", "mxfp4_status_string")
+           "mxfp4_row_to_fp8_col_grouped", "mxfp4_row_to_fp8_col_requant", "mxfp4_row_to_fp8_col_requant_grouped",
+           "mxfp4_status_string")
 
 _lib = None
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -44,6 +45,8 @@ def lib():
         L.mxfp4_row_to_col_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_row_to_fp8_col.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_row_to_fp8_col_grouped.argtypes = [_vp, _vp, _vp, _i32, _i64, _i64, _vp, _vp, _vp]
+        L.mxfp4_row_to_fp8_col_requant.argtypes = L.mxfp4_row_to_fp8_col.argtypes
+        L.mxfp4_row_to_fp8_col_requant_grouped.argtypes = L.mxfp4_row_to_fp8_col_grouped.argtypes
         for n in EXPORTS[:-1]:
             getattr(L, n).restype = ctypes.c_int
         L.mxfp4_status_string.argtypes = [ctypes.c_int]
@@ -180,8 +183,9 @@ def mxfp4_row_to_col_grouped(q_row, sf_row, expert_offsets, q_col=None, sf_col=N
     return q_col, sf_col
 
 
-def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=None):
-    """[M,K/2] + [M,K/32] row-blocked MXFP4 -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128])."""
+def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=None, requant=False):
+    """[M,K/2] + [M,K/32] row-blocked MXFP4 -> the transposed matrix as FP8: (E4M3 [K,M], float32 [K,M/128]).
+    requant=True calls mxfp4_row_to_fp8_col_requant (scale from the group maximum)."""
     _dev(q_row, torch.uint8, "q_row")
     _dev(sf_row, torch.uint8, "sf_row")
     M, K = q_row.shape[0], q_row.shape[1] * 2
@@ -189,13 +193,14 @@ def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=Non
         x_col = torch.empty((K, M), dtype=torch.uint8, device=q_row.device)
     if x_col_scale is None:
         x_col_scale = torch.empty((K, M // 128), dtype=torch.float32, device=q_row.device)
-    st = lib().mxfp4_row_to_fp8_col(q_row.data_ptr(), sf_row.data_ptr(), M, K, x_col.data_ptr(),
-                                    x_col_scale.data_ptr(), _stream(stream))
-    _check("mxfp4_row_to_fp8_col", st)
+    fn = lib().mxfp4_row_to_fp8_col_requant if requant else lib().mxfp4_row_to_fp8_col
+    st = fn(q_row.data_ptr(), sf_row.data_ptr(), M, K, x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream))
+    _check("mxfp4_row_to_fp8_col_requant" if requant else "mxfp4_row_to_fp8_col", st)
     return x_col, x_col_scale
 
 
-def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_col_scale=None, stream=None):
+def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_col_scale=None, stream=None,
+                                 requant=False):
     """Outputs are flat buffers: expert e's [K,T_e] at K*off_e, its float32 [K,ceil(T_e/128)] at
     K*sum_{j<e} ceil(T_j/128); any T_e.  A scale buffer allocated here has the upper-bound size
     K*(M//128 + num_experts)."""
@@ -208,8 +213,8 @@ def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_co
     if x_col_scale is None:
         x_col_scale = torch.empty(K * (M // 128 + expert_offsets.shape[0] - 1), dtype=torch.float32,
                                   device=q_row.device)
-    st = lib().mxfp4_row_to_fp8_col_grouped(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(),
-                                            expert_offsets.shape[0] - 1, M, K, x_col.data_ptr(),
-                                            x_col_scale.data_ptr(), _stream(stream))
-    _check("mxfp4_row_to_fp8_col_grouped", st)
+    fn = lib().mxfp4_row_to_fp8_col_requant_grouped if requant else lib().mxfp4_row_to_fp8_col_grouped
+    st = fn(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(), expert_offsets.shape[0] - 1, M, K,
+            x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream))
+    _check("mxfp4_row_to_fp8_col_requant_grouped" if requant else "mxfp4_row_to_fp8_col_grouped", st)
     return x_col, x_col_scale

@@ -125,7 +125,8 @@ mxfp4_status mxfp4_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_ro
 
 static mxfp4_status row_to_fp8_col_common(const uint8_t *q_row, const uint8_t *sf_row,
                                           const int32_t *expert_offsets, int32_t num_experts, int64_t M,
-                                          int64_t K, uint8_t *x_col, float *x_col_scale, void *hip_stream)
+                                          int64_t K, uint8_t *x_col, float *x_col_scale, void *hip_stream,
+                                          bool requant = false)
 {
     // the flat form has whole scale groups; the splits of the grouped form may have any length
     if (M < 0 || K < 0 || K % 128 != 0 || (!expert_offsets && M % 128 != 0))
@@ -141,8 +142,11 @@ static mxfp4_status row_to_fp8_col_common(const uint8_t *q_row, const uint8_t *s
     if (!aligned(q_row, 4) || !aligned(sf_row, 4) || !aligned(x_col, 16) || !aligned(x_col_scale, 4) ||
         (expert_offsets && !aligned(expert_offsets, 4)))
         return MXFP4_ERR_ALIGN;
-    return launched(mxfp4::launch_row_to_fp8_col(q_row, sf_row, expert_offsets, num_experts, M, K, x_col,
-                                                 x_col_scale, static_cast<hipStream_t>(hip_stream)));
+    const hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return launched(requant ? mxfp4::launch_row_to_fp8_col_requant(q_row, sf_row, expert_offsets, num_experts, M, K,
+                                                                   x_col, x_col_scale, stream)
+                            : mxfp4::launch_row_to_fp8_col(q_row, sf_row, expert_offsets, num_experts, M, K, x_col,
+                                                           x_col_scale, stream));
 }
 
 mxfp4_status mxfp4_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
@@ -161,6 +165,25 @@ mxfp4_status mxfp4_row_to_fp8_col_grouped(const uint8_t *q_row, const uint8_t *s
         return MXFP4_ERR_NULL;
     return row_to_fp8_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
                                  hip_stream);
+}
+
+mxfp4_status mxfp4_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                                          uint8_t *x_col, float *x_col_scale, void *hip_stream)
+{
+    return row_to_fp8_col_common(q_row, sf_row, nullptr, 0, M, K, x_col, x_col_scale, hip_stream, true);
+}
+
+mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const uint8_t *sf_row,
+                                                  const int32_t *expert_offsets, int32_t num_experts,
+                                                  int64_t M_total, int64_t K, uint8_t *x_col, float *x_col_scale,
+                                                  void *hip_stream)
+{
+    if (num_experts <= 0 || num_experts > MXFP4_MAX_EXPERTS)
+        return MXFP4_ERR_OFFSETS;
+    if (!expert_offsets)
+        return MXFP4_ERR_NULL;
+    return row_to_fp8_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
+                                 hip_stream, true);
 }
 
 const char *mxfp4_status_string(mxfp4_status status)

@@ -27,4 +27,9 @@ hipError_t launch_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, co
                                  int32_t num_experts, int64_t M, int64_t K, uint8_t *x_col, float *x_col_scale,
                                  hipStream_t stream);
 
+// The same conversion under the re-quantization reading (scale from the group maximum).
+hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
+                                         int32_t num_experts, int64_t M, int64_t K, uint8_t *x_col,
+                                         float *x_col_scale, hipStream_t stream);
+
 } // namespace mxfp4

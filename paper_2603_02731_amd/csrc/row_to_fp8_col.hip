@@ -19,6 +19,7 @@
 // scales: a 16-lane DPP reduction per k-block while staging, finished after the barrier.
 // The 8 x 32 B of a lane leave through an LDS tile whose 16-byte slots are rotated by the
 // column group (conflict-free writes, linear read-back) as full 256-byte rows.
+#include "fp8_col_tile.hpp"
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
@@ -58,11 +59,8 @@ constexpr int KBT = 8 / PARTS;           // k-blocks a thread stages
 constexpr int SPL = RPL / 16;            // 16-byte output slots of a lane per column
 constexpr int PHASES = MXFP4_F8C_PHASES; // the tile leaves in PHASES parts of 8/PHASES columns per lane
 constexpr int CP = 8 / PHASES;           // columns of a lane per phase
-constexpr int HALVES = 512 / T_THREADS;  // copy-out passes per LDS k-row index range of 32
 static_assert(RPL == 16 || RPL == 32, "a lane owns one or two 16-byte output slots per column");
 static_assert(PHASES == 1 || PHASES == 2 || PHASES == 4, "a phase is a whole number of nibble bytes");
-
-typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 struct Args {
     const uint8_t *q_row;
@@ -93,25 +91,6 @@ __device__ __forceinline__ uint32_t max_of_8_bytes(const uint8_t *p)
     const uint32_t t = max(max(v.x & 0xFFu, (v.x >> 8) & 0xFFu), max((v.x >> 16) & 0xFFu, v.x >> 24));
     const uint32_t u = max(max(v.y & 0xFFu, (v.y >> 8) & 0xFFu), max((v.y >> 16) & 0xFFu, v.y >> 24));
     return max(t, u);
-}
-
-// The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.
-__device__ __forceinline__ void store_head_bytes(uint8_t *dst, const u32x4 v, uint32_t n)
-{
-    uint32_t pos = 0; // bytes done
-    if (n & 8u) {
-        *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)v.y << 32) | v.x;
-        pos = 8;
-    }
-    if (n & 4u) {
-        *reinterpret_cast<u32_unaligned *>(dst + pos) = pos ? v.z : v.x;
-        pos += 4;
-    }
-    const uint32_t d = pos == 0u ? v.x : pos == 4u ? v.y : pos == 8u ? v.z : v.w; // the dword still open
-    if (n & 2u)
-        *reinterpret_cast<u16_unaligned *>(dst + pos) = (uint16_t)d;
-    if (n & 1u)
-        dst[pos + (n & 2u)] = (uint8_t)(d >> (8u * (n & 2u)));
 }
 
 } // namespace fp8col
@@ -324,50 +303,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         }
         __syncthreads();
 
-        // ---- write the part out: 16 lanes per k-row, 256 contiguous bytes.  Chunk u*T + tid of the
-        // LDS part is row c'*32 + cgx, physical slot tid%16, with cgx = tid/16 (plus 16 in the odd
-        // passes when T = 256).  Uniform k-row pointers plus one 32-bit lane offset (M <= 2^24).
-        {
-            const uint32_t pslot = tid & 15u;
-            const uint32_t lslot = (pslot - (tid >> 4)) & 15u; // 16 bytes = rows 16*lslot.. of the tile
-            const uint32_t lane_off = (tid >> 4) * 8u * (uint32_t)pitch_x + lslot * 16u;
-            uint8_t *krow0 = out_x + (size_t)(k0 + ph * CP) * pitch_x + m0;
-            // Rows on 32-byte boundaries (always, unless the splits are ragged) leave with non-temporal
-            // stores.  The others leave with plain, possibly unaligned vector stores and the L2 merges
-            // the pieces of neighbouring tiles: measured with 32 un-padded experts at [61440,7168]
-            // 204 us, against 258 us with non-temporal stores and 286 us with the rows realigned in
-            // registers (funnel shift of neighbouring 16-byte pieces, every store naturally aligned).
-            const bool streaming = MXFP4_F8C_NT != 0 && ((reinterpret_cast<uintptr_t>(out_x) | pitch_x) & 31u) == 0u;
-            // bytes of this lane's 16-byte piece that exist: 16, or fewer at the ragged end of a split
-            const uint32_t have = lslot * 16u < n_rows ? min(16u, n_rows - lslot * 16u) : 0u;
-            static_for<HALVES>([&](auto oddp) {
-                constexpr int odd = decltype(oddp)::value;
-                if ((odd * 16u + (tid >> 4)) * 8u < cols && have != 0u) {
-                    if (have == 16u && streaming) {
-#pragma unroll
-                        for (int c = 0; c < CP; ++c) {
-                            uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
-                            __builtin_nontemporal_store(s_out[(HALVES * c + odd) * T_THREADS + tid],
-                                                        reinterpret_cast<u32x4 *>(dst));
-                        }
-                    } else if (have == 16u) {
-                        // any alignment: global memory takes unaligned vector stores
-#pragma unroll
-                        for (int c = 0; c < CP; ++c) {
-                            uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
-                            *reinterpret_cast<u32x4_unaligned *>(dst) = s_out[(HALVES * c + odd) * T_THREADS + tid];
-                        }
-                    } else {
-#pragma nounroll
-                        for (int c = 0; c < CP; ++c) {
-                            uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
-                            const u32x4 v = s_out[(HALVES * c + odd) * T_THREADS + tid];
-                            store_head_bytes(dst, v, have);
-                        }
-                    }
-                }
-            });
-        }
+        write_part_out<CP, T_THREADS, MXFP4_F8C_NT != 0>(s_out, out_x + (size_t)(k0 + ph * CP) * pitch_x + m0, out_x,
+                                                         pitch_x, cols, n_rows, tid);
         if (ph + 1 < PHASES)
             __syncthreads(); // the LDS part is free again
     });

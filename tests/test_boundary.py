@@ -43,6 +43,9 @@ def test_argument_validation_without_a_gpu():
     assert L.mxfp4_row_to_col(a16, a16, 48, 128, a16, a16, None) == binding.ERR_SHAPE
     assert L.mxfp4_row_to_fp8_col(a16, a16, 96, 128, a16, a16, None) == binding.ERR_SHAPE
     assert L.mxfp4_row_to_fp8_col(a16, a16, 128, 1 << 25, a16, a16, None) == binding.ERR_SHAPE
+    assert L.mxfp4_row_to_fp8_col_requant(a16, a16, 96, 128, a16, a16, None) == binding.ERR_SHAPE
+    assert L.mxfp4_row_to_fp8_col_requant_grouped(a16, a16, a16, 0, 128, 128, a16, a16, None) == binding.ERR_OFFSETS
+    assert L.mxfp4_row_to_fp8_col_requant(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col(a16, a16, (1 << 24) + 128, 128, a16, a16, None) == binding.ERR_SHAPE
     # null pointers
     assert L.mxfp4_quant_from_fp8(None, a16, 4, 128, None, 4, a16, 64, a16, 4, None) == binding.ERR_NULL

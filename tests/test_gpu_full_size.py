@@ -102,6 +102,13 @@ def test_target_row_to_fp8_col_65536x7168(target):
     assert_same(host(x), wx, "target FP8 column bytes")
 
 
+def test_target_row_to_fp8_col_requant_65536x7168(target):
+    x, xs = mx.mxfp4_row_to_fp8_col(target["q"], target["sf"], requant=True)
+    wx, wxs = par.row_to_fp8_col(host(target["q"]), host(target["sf"]), requant=True)
+    assert_same(host(xs), wxs, "target FP8 column group scales (requant)")
+    assert_same(host(x), wx, "target FP8 column bytes (requant)")
+
+
 def test_config4_grouped_row_to_fp8_col_32_experts():
     off, counts = synth.expert_offsets(seed=3, num_experts=32, total_tokens=65536, pad_to=128)
     M, K = int(off[-1]), 2048

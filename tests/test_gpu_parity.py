@@ -412,3 +412,70 @@ def test_row_to_fp8_col_ragged_splits_without_padding(K):
     assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
     assert_same(sb[guard:guard + wxs.size], wxs, "ragged row->FP8 col: group scales")
     assert_same(xb[guard:guard + wx.size], wx, "ragged row->FP8 col: E4M3 bytes")
+
+
+# ------------------------------------------------------------------ the same under the re-quantization reading
+
+def check_row_to_fp8_col_requant(q, sf):
+    x, xs = mx.mxfp4_row_to_fp8_col(dev(q), dev(sf), requant=True)
+    wx, wxs = ref.row_to_fp8_col(q, sf, requant=True)
+    assert_same(host(xs), wxs, "row->FP8 col (requant): group scales")
+    assert_same(host(x), wx, "row->FP8 col (requant): E4M3 bytes")
+
+
+@pytest.mark.parametrize("M,K,center,spread,nan", [
+    (256, 256, 127, 0, 0.0), (384, 384, 127, 3, 0.0), (128, 128, 100, 8, 0.0), (640, 640, 30, 30, 0.0),
+    (128, 1152, 4, 6, 0.0), (384, 256, 250, 5, 0.0), (512, 512, 127, 127, 0.0), (384, 384, 120, 4, 0.003),
+    (256, 256, 120, 12, 0.05), (256, 384, 9, 4, 0.0)])
+def test_row_to_fp8_col_requant_random_codes_and_scale_spreads(M, K, center, spread, nan):
+    q, sf = synth.random_mxfp4(M, K, seed=M + K + spread + 1, scale_center=center, scale_spread=spread,
+                               nan_scale_frac=nan)
+    q, sf = q.numpy().copy(), sf.numpy()
+    q[:, 5] = 0                                   # two all-zero columns
+    q[7::32, :] &= 0x88                           # rows of signed zeros
+    q[:, 16:20] = np.where(np.random.default_rng(M).random((M, 4)) < 0.95, q[:, 16:20] & 0x88, q[:, 16:20])
+    check_row_to_fp8_col_requant(q, sf)
+
+
+def test_row_to_fp8_col_requant_every_shift_and_code():
+    K = 256
+    nib = np.tile(np.arange(16, dtype=np.uint8), K // 16)
+    qrow = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+    qs, sfs = [], []
+    for bmax, step in ((254, 1), (252, 1), (140, 1), (254, 2), (41, 1), (20, 1), (9, 1), (6, 1), (3, 1), (0, 1)):
+        b = np.clip(bmax - step * np.arange(128), 0, 254).astype(np.uint8)
+        sf = np.repeat(b[:, None], K // 32, axis=1)
+        sf[:, 1] = b[::-1]
+        sf[:, 2] = np.roll(b, 37)
+        qq = np.repeat(qrow[None], 128, axis=0).copy()
+        qq[::3, 40:48] &= 0x88                    # columns whose largest element is not in the largest-scale row
+        qs.append(qq)
+        sfs.append(sf)
+    check_row_to_fp8_col_requant(np.concatenate(qs), np.concatenate(sfs))
+
+
+def test_row_to_fp8_col_requant_on_quantized_swiglu():
+    x8, s = synth.swiglu_fp8(1024, 2048, seed=1)
+    q, sf = par.quant(x8.numpy(), s.numpy())
+    check_row_to_fp8_col_requant(q, sf)
+
+
+@pytest.mark.parametrize("K", [256, 384])
+def test_row_to_fp8_col_requant_ragged_splits(K):
+    T = [5, 0, 128, 256, 31, 257, 1, 300, 16, 15, 17, 511, 0, 130] + [0] * 60 + [128, 3]
+    off = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=41 + K, scale_center=118, scale_spread=9, nan_scale_frac=0.002)
+    q, sf = q.numpy(), sf.numpy()
+    sf[40:44, 0] = 254                                                    # beyond FP32 inside a partial tile
+    wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off, requant=True)
+    guard = 4096
+    xbuf = torch.full((guard + wx.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    sbuf = torch.full((guard + wxs.size + guard,), -7.0, dtype=torch.float32, device=DEV)
+    mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV), x_col=xbuf[guard:guard + wx.size],
+                                    x_col_scale=sbuf[guard:guard + wxs.size], requant=True)
+    xb, sb = host(xbuf), host(sbuf)
+    assert (xb[:guard] == 0xA5).all() and (xb[guard + wx.size:] == 0xA5).all(), "bytes written outside x_col"
+    assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
+    assert_same(sb[guard:guard + wxs.size], wxs, "ragged row->FP8 col (requant): group scales")
+    assert_same(xb[guard:guard + wx.size], wx, "ragged row->FP8 col (requant): E4M3 bytes")
