@@ -228,6 +228,35 @@ int mxfp4_ref_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *
     return 0;
 }
 
+/* The same quantizer with the routing turned around (section 3.2: quantization sits right before
+ * the dispatch, so a token is quantized once and its packed row goes to each of its experts):
+ * source row i is written to the output rows dst_idx[i*fanout + j], j < fanout; an entry outside
+ * [0, M_out) is skipped; output rows that no entry names are left as they are.  Every output row
+ * may be named at most once. */
+int mxfp4_ref_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                     const int32_t *dst_idx, int32_t fanout, int64_t M_out, uint8_t *q,
+                                     int64_t ld_q, uint8_t *sf, int64_t ld_sf)
+{
+    if (M_src < 0 || M_out < 0 || K < 0 || K % 128 != 0 || fanout <= 0)
+        return -1;
+    if (M_src == 0 || M_out == 0 || K == 0)
+        return 0;
+    if (!x || !x_scale || !dst_idx || !q || !sf || ld_q < K / 2 || ld_sf < K / 32)
+        return -1;
+    for (int64_t i = 0; i < M_src; ++i) {
+        for (int32_t j = 0; j < fanout; ++j) {
+            int64_t d = dst_idx[i * fanout + j];
+            if (d < 0 || d >= M_out)
+                continue;
+            int rc = mxfp4_ref_quant_from_fp8(x + i * K, x_scale + i * (K / 128), 1, K, NULL, 1, q + d * ld_q, ld_q,
+                                              sf + d * ld_sf, ld_sf);
+            if (rc)
+                return rc;
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- MXFP4 -> FP8 */
 
 /* Packed E2M1 [M,K/2] + UE8M0 [M,K/32]  ->  E4M3 [M,K] + FP32 scale per 1x128 tile

@@ -27,6 +27,8 @@ def lib():
             _build.build(force=True)
         L = ctypes.CDLL(path)
         L.mxfp4_ref_quant_from_fp8.argtypes = [_u8p, _f32p, _i64, _i64, _i32p, _i64, _u8p, _i64, _u8p, _i64]
+        L.mxfp4_ref_quant_from_fp8_scatter.argtypes = [_u8p, _f32p, _i64, _i64, _i32p, ctypes.c_int32, _i64, _u8p, _i64, _u8p, _i64]
+        L.mxfp4_ref_quant_from_fp8_scatter.restype = ctypes.c_int
         L.mxfp4_ref_quant_from_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint16), _i64, _i64, _u8p, _i64, _u8p, _i64]
         L.mxfp4_ref_quant_from_bf16.restype = ctypes.c_int
         L.mxfp4_ref_dequant_to_fp8.argtypes = [_u8p, _i64, _u8p, _i64, _i64, _i64, _u8p, _f32p]
@@ -87,6 +89,21 @@ def quant_from_fp8(x, x_scale, gather_idx=None):
     rc = lib().mxfp4_ref_quant_from_fp8(_p(x, _u8p), _p(x_scale, _f32p), M, K, gp, Mo,
                                         _p(q, _u8p), K // 2, _p(sf, _u8p), K // 32)
     _check(rc, "quant_from_fp8")
+    return q, sf
+
+
+def quant_from_fp8_scatter(x, x_scale, dst_idx, M_out, q=None, sf=None):
+    """Source row i -> output rows dst_idx[i, :] (entries outside [0, M_out) skipped).  q/sf: existing
+    [M_out,K/2] / [M_out,K/32] arrays to write into (rows not named keep their contents), else zeros."""
+    x = _c(x, np.uint8)
+    x_scale = _c(x_scale, np.float32)
+    dst_idx = _c(dst_idx, np.int32)
+    M, K = x.shape
+    q = np.zeros((M_out, K // 2), np.uint8) if q is None else q
+    sf = np.zeros((M_out, K // 32), np.uint8) if sf is None else sf
+    rc = lib().mxfp4_ref_quant_from_fp8_scatter(_p(x, _u8p), _p(x_scale, _f32p), M, K, _p(dst_idx, _i32p),
+                                                dst_idx.shape[1], M_out, _p(q, _u8p), K // 2, _p(sf, _u8p), K // 32)
+    _check(rc, "quant_from_fp8_scatter")
     return q, sf
 
 

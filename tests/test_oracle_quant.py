@@ -189,3 +189,33 @@ def test_grouped_equals_flat():
     # padding rows are zero blocks: zero scale byte
     lo, hi = int(off[0]) + int(counts[0]), int(off[1])
     assert not sf[lo:hi].any() and not q[lo:hi].any()
+
+
+def test_scatter_is_the_gather_turned_around():
+    # each source row to 3 output rows: the gather form (pinned above) with the inverse map gives the same rows;
+    # skipped entries and rows that nobody names are left alone
+    rng = np.random.default_rng(4)
+    x8, s = synth.tiny_roundtrip_fp8(seed=2)
+    x8, s = x8.numpy()[:40], s.numpy()[:40]
+    M, fan = x8.shape[0], 3
+    M_out = M * fan + 7
+    perm = rng.permutation(M_out)[:M * fan].reshape(M, fan).astype(np.int32)
+    perm[5, 1] = -1                                          # skipped
+    perm[9, 0] = M_out + 3                                   # out of range: skipped
+    q0 = rng.integers(0, 256, size=(M_out, x8.shape[1] // 2)).astype(np.uint8)
+    sf0 = rng.integers(0, 255, size=(M_out, x8.shape[1] // 32)).astype(np.uint8)
+    q, sf = ref.quant_from_fp8_scatter(x8, s, perm, M_out, q=q0.copy(), sf=sf0.copy())
+    named = np.zeros(M_out, bool)
+    for i in range(M):
+        for d in perm[i]:
+            if 0 <= d < M_out:
+                named[d] = True
+    src_of = np.zeros(M_out, np.int32)
+    for i in range(M):
+        for d in perm[i]:
+            if 0 <= d < M_out:
+                src_of[d] = i
+    wq, wsf = ref.quant_from_fp8(x8, s, gather_idx=src_of)
+    assert named.sum() == M * fan - 2
+    assert (q[named] == wq[named]).all() and (sf[named] == wsf[named]).all()
+    assert (q[~named] == q0[~named]).all() and (sf[~named] == sf0[~named]).all()
