@@ -234,7 +234,7 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
                                        M * K * (2.0 + 0.53125))
         del xbf, qb, sb
 
-    if want("quant_gather_top8") or want("quant_gather_top8_records"):
+    if want("quant_gather_top8") or want("quant_gather_top8_records") or want("quant_scatter_top8"):
         top_k = 8
         idx = synth.routing_indices(seed=a.seed, num_tokens=M, top_k=top_k, device=dev)
         Mo = idx.shape[0]
@@ -248,6 +248,15 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
                                         "compulsory_GB/s": compulsory / us * 1e-3,
                                         "frac_of_hbm_peak_compulsory": compulsory / us * 1e-3 / HBM_PEAK_GBPS}
             del qg, sg
+        if want("quant_scatter_top8"):
+            # the same payload with every token quantized once and written to its 8 destinations
+            dst = torch.argsort(idx.long(), stable=True).to(torch.int32).view(M, top_k).contiguous()
+            qg = torch.empty((Mo, K // 2), dtype=torch.uint8, device=dev)
+            sg = torch.empty((Mo, K // 32), dtype=torch.uint8, device=dev)
+            us = timed(lambda: mx.mxfp4_quant_from_fp8_scatter(x8, s, dst, Mo, q=qg, sf=sg))
+            res["quant_scatter_top8"] = {"us": us, "compulsory_GB/s": compulsory / us * 1e-3,
+                                         "frac_of_hbm_peak_compulsory": compulsory / us * 1e-3 / HBM_PEAK_GBPS}
+            del qg, sg, dst
         if want("quant_gather_top8_records"):
             rec = K // 2 + K // 32
             buf = torch.empty(Mo * rec, dtype=torch.uint8, device=dev)

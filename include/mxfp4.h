@@ -72,6 +72,19 @@ mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_
                                   const int32_t *gather_idx, int64_t M_out, uint8_t *q,
                                   int64_t ld_q, uint8_t *sf, int64_t ld_sf, void *hip_stream);
 
+/* The same quantizer with the routing turned around (paper sec. 3.2: quantization sits right before
+ * the dispatch): a token is read and quantized ONCE and its packed row written to each of its
+ * destinations, instead of once per destination as with gather_idx.
+ *   x, x_scale  as above, [M_src, K] and [M_src, K/128], dense
+ *   dst_idx     int32 [M_src, fanout] on the device: source row i is written to the output rows
+ *               dst_idx[i*fanout + j], j < fanout; an entry outside [0, M_out) is skipped.  Every
+ *               output row may be named at most once (otherwise which copy it ends up holding is
+ *               unspecified); output rows that no entry names keep their contents.
+ *   q, ld_q, sf, ld_sf   M_out output rows, as above (planes or per-token records).  fanout >= 1. */
+mxfp4_status mxfp4_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                          const int32_t *dst_idx, int32_t fanout, int64_t M_out, uint8_t *q,
+                                          int64_t ld_q, uint8_t *sf, int64_t ld_sf, void *hip_stream);
+
 /* BF16 -> MXFP4: the row-wise quantizer as the paper states it (sec. 3.1, BF16ToFP4Row): the same
  * scale rule and rounding, applied to the BF16 values themselves.  NaN -> block scale 0xFF, codes 0;
  * +-inf -> block scale 254, code 7.

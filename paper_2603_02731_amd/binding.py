@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libmxfp4.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_OFFSETS, ERR_LAUNCH = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
+EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_fp8_scatter", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
            "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_row_to_fp8_col",
            "mxfp4_row_to_fp8_col_grouped", "mxfp4_row_to_fp8_col_requant", "mxfp4_row_to_fp8_col_requant_grouped",
            "mxfp4_status_string")
@@ -38,6 +38,7 @@ def lib():
             _build.build(force=True)
         L = ctypes.CDLL(LIB_PATH)  # raises OSError if it cannot be loaded: no fallback
         L.mxfp4_quant_from_fp8.argtypes = [_vp, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp]
+        L.mxfp4_quant_from_fp8_scatter.argtypes = [_vp, _vp, _i64, _i64, _vp, _i32, _i64, _vp, _i64, _vp, _i64, _vp]
         L.mxfp4_quant_from_bf16.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp]
         L.mxfp4_dequant_to_fp8.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
         L.mxfp4_row_to_col.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp]
@@ -101,6 +102,26 @@ def mxfp4_quant_from_fp8(x, x_scale, gather_idx=None, q=None, sf=None, ld_q=None
                                     None if gather_idx is None else gather_idx.data_ptr(), M_out,
                                     q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream))
     _check("mxfp4_quant_from_fp8", st)
+    return q, sf
+
+
+def mxfp4_quant_from_fp8_scatter(x, x_scale, dst_idx, M_out, q=None, sf=None, ld_q=None, ld_sf=None, stream=None):
+    """Source row i of x -> output rows dst_idx[i, :] (int32 [M_src, fanout]; entries outside [0, M_out) are
+    skipped).  Newly allocated q/sf are zero-filled, since rows that no entry names are not written."""
+    _dev(x, torch.uint8, "x")
+    _dev(x_scale, torch.float32, "x_scale")
+    _dev(dst_idx, torch.int32, "dst_idx")
+    M_src, K = x.shape
+    if q is None:
+        q = torch.zeros((M_out, K // 2), dtype=torch.uint8, device=x.device)
+    if sf is None:
+        sf = torch.zeros((M_out, K // 32), dtype=torch.uint8, device=x.device)
+    ld_q = K // 2 if ld_q is None else ld_q
+    ld_sf = K // 32 if ld_sf is None else ld_sf
+    st = lib().mxfp4_quant_from_fp8_scatter(x.data_ptr(), x_scale.data_ptr(), M_src, K, dst_idx.data_ptr(),
+                                            dst_idx.shape[1], M_out, q.data_ptr(), ld_q, sf.data_ptr(), ld_sf,
+                                            _stream(stream))
+    _check("mxfp4_quant_from_fp8_scatter", st)
     return q, sf
 
 

@@ -40,6 +40,26 @@ mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_
                                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+mxfp4_status mxfp4_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                          const int32_t *dst_idx, int32_t fanout, int64_t M_out, uint8_t *q,
+                                          int64_t ld_q, uint8_t *sf, int64_t ld_sf, void *hip_stream)
+{
+    if (M_src < 0 || M_out < 0 || K < 0 || K % 128 != 0 || fanout <= 0)
+        return MXFP4_ERR_SHAPE;
+    if (M_src == 0 || M_out == 0 || K == 0)
+        return MXFP4_OK;
+    if (!x || !x_scale || !dst_idx || !q || !sf)
+        return MXFP4_ERR_NULL;
+    if (ld_q < K / 2 || ld_sf < K / 32 || M_src >= kMaxRows || M_out >= kMaxRows || K >= kMaxRows ||
+        M_src * (K / 16) >= kMaxWorkItems)
+        return MXFP4_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(x_scale, 4) || !aligned(q, 8) || ld_q % 8 != 0 || !aligned(sf, 4) ||
+        ld_sf % 4 != 0 || !aligned(dst_idx, 4))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_quant_from_fp8_scatter(x, x_scale, M_src, K, dst_idx, fanout, M_out, q, ld_q, sf,
+                                                         ld_sf, static_cast<hipStream_t>(hip_stream)));
+}
+
 mxfp4_status mxfp4_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *q, int64_t ld_q, uint8_t *sf,
                                    int64_t ld_sf, void *hip_stream)
 {

@@ -11,6 +11,11 @@ hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t
                                  const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
                                  uint8_t *sf, int64_t ld_sf, hipStream_t stream);
 
+// Source row i goes to the output rows dst_idx[i*fanout .. i*fanout + fanout - 1].
+hipError_t launch_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                         const int32_t *dst_idx, int32_t fanout, int64_t M_out, uint8_t *q,
+                                         int64_t ld_q, uint8_t *sf, int64_t ld_sf, hipStream_t stream);
+
 hipError_t launch_quant_from_bf16(const uint16_t *x, int64_t M, int64_t K, uint8_t *q, int64_t ld_q, uint8_t *sf,
                                   int64_t ld_sf, hipStream_t stream);
 

@@ -140,6 +140,86 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
     }
 }
 
+// The routing turned around: every source row is read and quantized once and written to each of
+// its `fanout` destination rows (a token and its top-k experts), instead of being read and
+// quantized again for every destination.  Same lane layout; dense source, strided outputs.
+struct QuantScatterArgs {
+    const uint8_t *x;
+    const float *x_scale;
+    const int32_t *dst_idx; // [M_src, fanout]
+    uint8_t *q;
+    uint8_t *sf;
+    int64_t ld_q;
+    int64_t ld_sf;
+    uint32_t n_chunks;       // M_src * K / 16
+    uint32_t chunks_per_row; // K / 16
+    uint32_t fanout;
+    uint32_t M_out;
+};
+
+__global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_scatter_kernel(const QuantScatterArgs a)
+{
+    const uint32_t c0 = blockIdx.x * (QUANT_THREADS * QUANT_UNROLL) + threadIdx.x;
+
+    u32x4 w[QUANT_UNROLL];
+    float s[QUANT_UNROLL];
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        const uint32_t c = c0 + u * QUANT_THREADS;
+        if (c >= a.n_chunks)
+            break; // n_chunks is a multiple of 8: the 8 lanes of a tile leave together
+        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.x + (size_t)c * 16));
+        s[u] = a.x_scale[c >> 3];
+    }
+
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        const uint32_t c = c0 + u * QUANT_THREADS;
+        if (c >= a.n_chunks)
+            break;
+        uint32_t out[2], b;
+        quant16(w[u], s[u], out, &b);
+        // lanes 2j, 2j+1 of the tile's 8 hold block j's byte: gather the four into lane 0
+        uint32_t t = b | (dpp_read<DPP_QUAD_XOR2>(b) << 8); // lanes 0,1: B0 | B1 << 8
+        t |= row_shift_left4(t) << 16;                       // lane 0: ... | B2 << 16 | B3 << 24
+
+        const uint32_t row = c / a.chunks_per_row;
+        const uint32_t cc = c - row * a.chunks_per_row;
+        const int32_t *dst = a.dst_idx + (size_t)row * a.fanout;
+        for (uint32_t j = 0; j < a.fanout; ++j) {
+            const uint32_t d = (uint32_t)dst[j];
+            if (d >= a.M_out) // also skips negative entries
+                continue;
+            __builtin_nontemporal_store(u32x2{out[0], out[1]},
+                                        reinterpret_cast<u32x2 *>(a.q + (size_t)d * a.ld_q + (size_t)cc * 8));
+            if ((threadIdx.x & 7u) == 0u)
+                *reinterpret_cast<uint32_t *>(a.sf + (size_t)d * a.ld_sf + (size_t)(cc >> 3) * 4) = t;
+        }
+    }
+}
+
+hipError_t launch_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
+                                         const int32_t *dst_idx, int32_t fanout, int64_t M_out, uint8_t *q,
+                                         int64_t ld_q, uint8_t *sf, int64_t ld_sf, hipStream_t stream)
+{
+    QuantScatterArgs a;
+    a.x = x;
+    a.x_scale = x_scale;
+    a.dst_idx = dst_idx;
+    a.q = q;
+    a.sf = sf;
+    a.ld_q = ld_q;
+    a.ld_sf = ld_sf;
+    a.n_chunks = (uint32_t)(M_src * (K / 16));
+    a.chunks_per_row = (uint32_t)(K / 16);
+    a.fanout = (uint32_t)fanout;
+    a.M_out = (uint32_t)M_out;
+    constexpr uint32_t per_block = QUANT_THREADS * QUANT_UNROLL;
+    const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
+    hipLaunchKernelGGL(quant_from_fp8_scatter_kernel, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
                                  const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
                                  uint8_t *sf, int64_t ld_sf, hipStream_t stream)

@@ -47,6 +47,9 @@ def test_argument_validation_without_a_gpu():
     assert L.mxfp4_row_to_fp8_col_requant_grouped(a16, a16, a16, 0, 128, 128, a16, a16, None) == binding.ERR_OFFSETS
     assert L.mxfp4_row_to_fp8_col_requant(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col(a16, a16, (1 << 24) + 128, 128, a16, a16, None) == binding.ERR_SHAPE
+    assert L.mxfp4_quant_from_fp8_scatter(a16, a16, 4, 128, a16, 0, 4, a16, 64, a16, 4, None) == binding.ERR_SHAPE
+    assert L.mxfp4_quant_from_fp8_scatter(a16, a16, 4, 128, None, 2, 8, a16, 64, a16, 4, None) == binding.ERR_NULL
+    assert L.mxfp4_quant_from_fp8_scatter(a16, a16, 0, 128, None, 2, 8, None, 64, None, 4, None) == binding.OK
     # null pointers
     assert L.mxfp4_quant_from_fp8(None, a16, 4, 128, None, 4, a16, 64, a16, 4, None) == binding.ERR_NULL
     assert L.mxfp4_dequant_to_fp8(a16, 64, None, 4, 4, 128, a16, a16, None) == binding.ERR_NULL

@@ -140,6 +140,12 @@ def test_config5_dispatch_payload_round_trip(target):
         sl = slice(lo, lo + 65536)
         assert torch.equal(recs[sl, : K // 2], qsrc[li[sl]])
         assert torch.equal(recs[sl, K // 2:], sfsrc[li[sl]])
+    # the same payload by the scatter form (every token quantized once): byte for byte the same records
+    dst = torch.argsort(li, stable=True).to(torch.int32).view(M, top_k).contiguous()
+    buf2 = torch.zeros(Mo * rec, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8_scatter(x8, s, dst, Mo, q=buf2, sf=buf2[K // 2:], ld_q=rec, ld_sf=rec)
+    assert torch.equal(buf2, buf)
+    del buf2, dst
     # sampled rows straight against the oracle (gathered form)
     g = torch.Generator().manual_seed(7)
     rows = torch.randperm(Mo, generator=g)[:4096].sort().values

@@ -479,3 +479,31 @@ def test_row_to_fp8_col_requant_ragged_splits(K):
     assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
     assert_same(sb[guard:guard + wxs.size], wxs, "ragged row->FP8 col (requant): group scales")
     assert_same(xb[guard:guard + wx.size], wx, "ragged row->FP8 col (requant): E4M3 bytes")
+
+
+# ------------------------------------------------------------------ the quantizer with the routing turned around
+
+def test_quant_scatter_equals_gather_and_leaves_other_rows_alone():
+    rng = np.random.default_rng(8)
+    M, K, fan = 300, 768, 4
+    x8, s = synth.student_t_fp8(M, K, seed=3)
+    x8, s = x8.numpy(), s.numpy()
+    M_out = M * fan + 11
+    perm = rng.permutation(M_out)[:M * fan].reshape(M, fan).astype(np.int32)
+    perm[5, 1] = -1
+    perm[9, 0] = M_out + 3
+    q0 = rng.integers(0, 256, size=(M_out, K // 2)).astype(np.uint8)
+    sf0 = rng.integers(0, 255, size=(M_out, K // 32)).astype(np.uint8)
+    wq, wsf = ref.quant_from_fp8_scatter(x8, s, perm, M_out, q=q0.copy(), sf=sf0.copy())
+    q, sf = mx.mxfp4_quant_from_fp8_scatter(dev(x8), dev(s), dev(perm), M_out, q=dev(q0), sf=dev(sf0))
+    assert_same(host(sf), wsf, "scatter: scale bytes")
+    assert_same(host(q), wq, "scatter: nibbles")
+    # into per-token records (nibbles then scales), fan-out 1 = a permutation
+    rec = K // 2 + K // 32
+    one = rng.permutation(M).astype(np.int32).reshape(M, 1)
+    buf = torch.zeros(M * rec, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8_scatter(dev(x8), dev(s), dev(one), M, q=buf, sf=buf[K // 2:], ld_q=rec, ld_sf=rec)
+    got = host(buf).reshape(M, rec)
+    fq, fsf = ref.quant_from_fp8(x8, s)
+    assert_same(got[one[:, 0], : K // 2], fq, "scatter into records: nibbles")
+    assert_same(got[one[:, 0], K // 2:], fsf, "scatter into records: scale bytes")
