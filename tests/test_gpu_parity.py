@@ -507,3 +507,55 @@ def test_quant_scatter_equals_gather_and_leaves_other_rows_alone():
     fq, fsf = ref.quant_from_fp8(x8, s)
     assert_same(got[one[:, 0], : K // 2], fq, "scatter into records: nibbles")
     assert_same(got[one[:, 0], K // 2:], fsf, "scatter into records: scale bytes")
+
+
+# ------------------------------------------------------------------ streams and graphs
+
+def test_side_stream_and_graph_replays():
+    # the library only enqueues kernels on the stream it is given: it runs on a side stream and under
+    # HIP graph capture; every replay (with new input contents between replays) equals the eager result
+    M, K = 512, 1024
+    gen = [synth.student_t_fp8(M, K, seed=sd) for sd in (0, 1, 2)]
+    x8 = torch.empty((M, K), dtype=torch.uint8, device=DEV)
+    s = torch.empty((M, K // 128), dtype=torch.float32, device=DEV)
+    q = torch.empty((M, K // 2), dtype=torch.uint8, device=DEV)
+    sf = torch.empty((M, K // 32), dtype=torch.uint8, device=DEV)
+    xb = torch.empty((M, K), dtype=torch.uint8, device=DEV)
+    sb = torch.empty((M, K // 128), dtype=torch.float32, device=DEV)
+    qc = torch.empty((K, M // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.empty((K, M // 32), dtype=torch.uint8, device=DEV)
+    xc = torch.empty((K, M), dtype=torch.uint8, device=DEV)
+    xcs = torch.empty((K, M // 128), dtype=torch.float32, device=DEV)
+
+    def path(stream):
+        mx.mxfp4_quant_from_fp8(x8, s, q=q, sf=sf, stream=stream)
+        mx.mxfp4_dequant_to_fp8(q, sf, x=xb, x_scale=sb, stream=stream)
+        mx.mxfp4_row_to_col(q, sf, q_col=qc, sf_col=sc, stream=stream)
+        mx.mxfp4_row_to_fp8_col(q, sf, x_col=xc, x_col_scale=xcs, stream=stream)
+
+    side = torch.cuda.Stream()
+    x8.copy_(gen[0][0])
+    s.copy_(gen[0][1])
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        path(side)                                      # warm-up on the side stream, eager
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        path(torch.cuda.current_stream())
+    for xs8, ss in gen:
+        xh, sh = xs8.numpy(), ss.numpy()
+        x8.copy_(xs8)
+        s.copy_(ss)
+        for t in (q, sf, xb, sb, qc, sc, xc, xcs):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        wq, wsf = ref.quant_from_fp8(xh, sh)
+        wx, wxs = ref.dequant_to_fp8(wq, wsf)
+        wqc, wsc = ref.row_to_col(wq, wsf)
+        wxc, wxcs = ref.row_to_fp8_col(wq, wsf)
+        for got, want, name in ((q, wq, "q"), (sf, wsf, "sf"), (xb, wx, "x"), (sb, wxs, "x_scale"), (qc, wqc, "q_col"),
+                                (sc, wsc, "sf_col"), (xc, wxc, "x_col"), (xcs, wxcs, "x_col_scale")):
+            assert_same(host(got), want, f"graph replay: {name}")
