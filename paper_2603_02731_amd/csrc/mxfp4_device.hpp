@@ -87,6 +87,17 @@ __device__ __forceinline__ uint32_t ue8m0_of_block_max(uint32_t gmax_bits)
     return (uint32_t)b;
 }
 
+// Scale operand of row I of a 32-row slice whose UE8M0 bytes are packed four to a dword (byte
+// I%4 of dword I/4): the byte moved into bits 30:23 with one shift.  What lands in the sign and
+// mantissa bits belongs to the neighbouring bytes; the conversion instructions read the exponent
+// field only.
+template <int I>
+__device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
+{
+    constexpr int j = I & 3;
+    return u2f(j == 3 ? sb[I >> 2] >> 1 : sb[I >> 2] << (23 - 8 * j));
+}
+
 // Workgroup -> tile for the transposing kernels.  The hardware deals consecutive workgroup ids
 // round-robin to the 8 XCDs, each with its own L2.  Id i therefore takes entry i/8 of XCD (i%8)'s
 // own contiguous share of a tile order in which MBM x MBK tiles form a macro block walked

@@ -59,16 +59,6 @@ struct RowToColArgs {
 
 constexpr uint32_t MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK; // macro block of the tile order
 
-// Scale operand of row I of a slice: its UE8M0 byte (byte I%4 of dword I/4) moved into bits
-// 30:23 with one shift.  What lands in the sign and mantissa bits belongs to the neighbouring
-// bytes; the conversion instructions read the exponent field only.
-template <int I>
-__device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
-{
-    constexpr int j = I & 3;
-    return u2f(j == 3 ? sb[I >> 2] >> 1 : sb[I >> 2] << (23 - 8 * j));
-}
-
 // One lane's 32x8 slice through the hardware conversions.  Exact while every value
 // e2m1 * 2^(b-127) is an FP32 number, i.e. for row-scale bytes up to 252
 // (6 * 2^125 < 2^128; the smallest, 0.5 * 2^-127, is an FP32 subnormal).

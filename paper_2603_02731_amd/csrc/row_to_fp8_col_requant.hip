@@ -45,16 +45,6 @@ struct Args {
     uint32_t tiles_k; // 256-column tiles
 };
 
-// Scale operand of row I of a slice: its UE8M0 byte (byte I%4 of dword I/4) moved into bits
-// 30:23 with one shift.  What lands in the sign and mantissa bits belongs to the neighbouring
-// bytes; the conversion instructions read the exponent field only.
-template <int I>
-__device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
-{
-    constexpr int j = I & 3;
-    return u2f(j == 3 ? sb[I >> 2] >> 1 : sb[I >> 2] << (23 - 8 * j));
-}
-
 // Emax = biased exponent of a non-zero column maximum, plus one (FP32 subnormals: 2^-127 and
 // 1.5 * 2^-127 give 1, 2^-128 gives 0).
 __device__ __forceinline__ int emax_of_amax_bits(uint32_t bits)
