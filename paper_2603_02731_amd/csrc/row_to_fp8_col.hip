@@ -31,8 +31,10 @@ namespace mxfp4 {
 #ifndef MXFP4_F8C_PHASES
 #define MXFP4_F8C_PHASES 1
 #endif
+// macro block of the tile order: 16 x 4 tiles (32 x 4 is as fast on one big matrix, 16 x 4 is
+// 4-5 % faster on experts of 2048 or 4096 rows, whose row tiles then fill whole macro blocks)
 #ifndef MXFP4_F8C_MBM
-#define MXFP4_F8C_MBM 32
+#define MXFP4_F8C_MBM 16
 #endif
 #ifndef MXFP4_F8C_MBK
 #define MXFP4_F8C_MBK 4
