@@ -322,12 +322,49 @@ int mxfp4_ref_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, 
 /* ---------------------------------------------------------------- row-blocked -> column-blocked */
 
 /* Row-blocked MXFP4 (nibbles [M,K/2], 1x32 scales [M,K/32]) -> column-blocked MXFP4 of
- * the same matrix, stored transposed: nibbles [K,M/2] (low nibble = even m) and 32x1
- * scales [K,M/32].  Definition (section 3.4: de-quantization, transposition and
+ * the same matrix, stored transposed: nibbles [K,ceil(M/2)] (low nibble = even m) and 32x1
+ * scales [K,ceil(M/32)].  Definition (section 3.4: de-quantization, transposition and
  * re-quantization in one pass): every element takes its exact real value
  * +-e2m1(code) * 2^(b_row - 127); each run of 32 consecutive m at fixed k is then
- * quantized with the scale rule and rounding of section 3.1.  M % 32 == 0.
- * A NaN row scale poisons every column block it touches. */
+ * quantized with the scale rule and rounding of section 3.1.  A last run of fewer than 32 rows
+ * (ragged splits only) is quantized over the rows it has; with an odd M the unused high nibble
+ * of a k-row's last byte is 0.  A NaN row scale poisons every column block it touches. */
+static void col_blocks_of_rows(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
+                               uint8_t *q_col, uint8_t *sf_col)
+{
+    const int64_t B = (M + 31) / 32, P = (M + 1) / 2; /* blocks and bytes per output row */
+    for (int64_t k = 0; k < K; ++k) {
+        for (int64_t mb = 0; mb < B; ++mb) {
+            const int n = (int)(M - mb * 32 < 32 ? M - mb * 32 : 32);
+            double v[32];
+            int has_nan = 0;
+            for (int e = 0; e < 32; ++e) {
+                v[e] = 0.0; /* rows that do not exist count as zeros and are not stored */
+                if (e >= n)
+                    continue;
+                int64_t m = mb * 32 + e;
+                unsigned byte = q_row[m * (K / 2) + k / 2];
+                unsigned nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
+                unsigned b = sf_row[m * (K / 32) + k / 32];
+                if (b == 0xFFu) {
+                    has_nan = 1;
+                    continue;
+                }
+                double a = ldexp(e2m1_magnitude(nib & 7u), (int)b - 127);
+                v[e] = (nib & 8u) ? -a : a;
+            }
+            unsigned char code[32];
+            unsigned bc = quantize_block32(v, has_nan, code);
+            sf_col[k * B + mb] = (uint8_t)bc;
+            for (int e = 0; e < (n + 1) / 2; ++e) {
+                unsigned hi = 2 * e + 1 < n ? code[2 * e + 1] : 0u;
+                q_col[k * P + mb * 16 + e] = (uint8_t)(code[2 * e] | (hi << 4));
+            }
+        }
+    }
+}
+
+/* The flat conversion: M % 32 == 0. */
 int mxfp4_ref_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M, int64_t K,
                          uint8_t *q_col, uint8_t *sf_col)
 {
@@ -337,31 +374,7 @@ int mxfp4_ref_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64_t M,
         return 0;
     if (!q_row || !sf_row || !q_col || !sf_col)
         return -1;
-
-    for (int64_t k = 0; k < K; ++k) {
-        for (int64_t mb = 0; mb < M / 32; ++mb) {
-            double v[32];
-            int has_nan = 0;
-            for (int e = 0; e < 32; ++e) {
-                int64_t m = mb * 32 + e;
-                unsigned byte = q_row[m * (K / 2) + k / 2];
-                unsigned nib = (k & 1) ? (byte >> 4) : (byte & 0xFu);
-                unsigned b = sf_row[m * (K / 32) + k / 32];
-                if (b == 0xFFu) {
-                    has_nan = 1;
-                    v[e] = 0.0;
-                    continue;
-                }
-                double a = ldexp(e2m1_magnitude(nib & 7u), (int)b - 127);
-                v[e] = (nib & 8u) ? -a : a;
-            }
-            unsigned char code[32];
-            unsigned bc = quantize_block32(v, has_nan, code);
-            sf_col[k * (M / 32) + mb] = (uint8_t)bc;
-            for (int e = 0; e < 16; ++e)
-                q_col[k * (M / 2) + mb * 16 + e] = (uint8_t)(code[2 * e] | (code[2 * e + 1] << 4));
-        }
-    }
+    col_blocks_of_rows(q_row, sf_row, M, K, q_col, sf_col);
     return 0;
 }
 
@@ -504,14 +517,14 @@ int mxfp4_ref_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row
 /* ---------------------------------------------------------------- ragged (per-expert) variants */
 
 /* expert_offsets[0..num_experts]: rows [off_e, off_{e+1}) belong to expert e (section 3.4,
- * ragged MoE tensors).  off_0 = 0, off_E = M_total, non-decreasing, each T_e % 32 == 0.
+ * ragged MoE tensors).  off_0 = 0, off_E = M_total, non-decreasing; any T_e >= 0.
  * Quantization is row-independent, so the grouped form is the flat form on M_total rows. */
 static int offsets_ok(const int32_t *off, int32_t E, int64_t M_total)
 {
     if (E <= 0 || !off || off[0] != 0 || (int64_t)off[E] != M_total)
         return 0;
     for (int32_t e = 0; e < E; ++e)
-        if (off[e + 1] < off[e] || (off[e + 1] - off[e]) % 32 != 0)
+        if (off[e + 1] < off[e])
             return 0;
     return 1;
 }
@@ -533,22 +546,32 @@ int mxfp4_ref_quant_from_fp8_grouped(const uint8_t *x, const float *x_scale,
     return 0;
 }
 
-/* Expert e's output is its own dense [K, T_e/2] and [K, T_e/32] matrices, stored back to
- * back at byte offsets K*off_e/2 and K*off_e/32: contiguous storage without padding. */
+/* Ragged splits without padding (section 3.4): any T_e >= 0.  Expert e's output is its own dense
+ * [K, ceil(T_e/2)] and [K, ceil(T_e/32)] matrices, stored back to back at byte offsets
+ * K * sum_{j<e} ceil(T_j/2) and K * sum_{j<e} ceil(T_j/32) (= K*off_e/2 and K*off_e/32 when every
+ * T_e is a multiple of 32). */
 int mxfp4_ref_row_to_col_grouped(const uint8_t *q_row, const uint8_t *sf_row,
                                  const int32_t *expert_offsets, int32_t num_experts,
                                  int64_t M_total, int64_t K, uint8_t *q_col, uint8_t *sf_col)
 {
-    if (!offsets_ok(expert_offsets, num_experts, M_total) || K < 0 || K % 128 != 0)
+    if (num_experts <= 0 || !expert_offsets || expert_offsets[0] != 0 ||
+        (int64_t)expert_offsets[num_experts] != M_total || K < 0 || K % 128 != 0)
         return -1;
+    for (int32_t e = 0; e < num_experts; ++e)
+        if (expert_offsets[e + 1] < expert_offsets[e])
+            return -1;
+    if (M_total == 0 || K == 0)
+        return 0;
+    if (!q_row || !sf_row || !q_col || !sf_col)
+        return -1;
+    int64_t bytes_before = 0, blocks_before = 0;
     for (int32_t e = 0; e < num_experts; ++e) {
         int64_t o = expert_offsets[e], T = expert_offsets[e + 1] - o;
-        int rc = mxfp4_ref_row_to_col(q_row ? q_row + o * (K / 2) : q_row,
-                                      sf_row ? sf_row + o * (K / 32) : sf_row, T, K,
-                                      q_col ? q_col + o * (K / 2) : q_col,
-                                      sf_col ? sf_col + o * (K / 32) : sf_col);
-        if (rc)
-            return rc;
+        if (T > 0)
+            col_blocks_of_rows(q_row + o * (K / 2), sf_row + o * (K / 32), T, K, q_col + bytes_before * K,
+                               sf_col + blocks_before * K);
+        bytes_before += (T + 1) / 2;
+        blocks_before += (T + 31) / 32;
     }
     return 0;
 }

@@ -188,13 +188,15 @@ def quant_from_fp8_grouped(x, x_scale, expert_offsets):
 
 
 def row_to_col_grouped(q_row, sf_row, expert_offsets):
-    """Flat byte buffers: expert e's [K,T_e/2] at K*off_e/2, its [K,T_e/32] at K*off_e/32."""
+    """Flat byte buffers: expert e's [K,ceil(T_e/2)] at K*sum_{j<e} ceil(T_j/2), its [K,ceil(T_e/32)] at
+    K*sum_{j<e} ceil(T_j/32) (K*off_e/2 and K*off_e/32 for multiples of 32).  Any T_e >= 0."""
     q_row = _c(q_row, np.uint8)
     sf_row = _c(sf_row, np.uint8)
     off = _c(expert_offsets, np.int32)
     M, K = q_row.shape[0], q_row.shape[1] * 2
-    qc = np.empty(M * K // 2, np.uint8)
-    sc = np.empty(M * K // 32, np.uint8)
+    T = np.diff(off.astype(np.int64))
+    qc = np.empty(int(((T + 1) // 2).sum()) * K, np.uint8)
+    sc = np.empty(int(((T + 31) // 32).sum()) * K, np.uint8)
     rc = lib().mxfp4_ref_row_to_col_grouped(_p(q_row, _u8p), _p(sf_row, _u8p), _p(off, _i32p),
                                             off.shape[0] - 1, M, K, _p(qc, _u8p), _p(sc, _u8p))
     _check(rc, "row_to_col_grouped")

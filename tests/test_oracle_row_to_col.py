@@ -121,3 +121,52 @@ def test_grouped_equals_flat_per_expert():
         wq, ws = ref.row_to_col(q[lo:hi], sf[lo:hi])
         assert (qg[K * lo // 2: K * hi // 2].reshape(K, (hi - lo) // 2) == wq).all()
         assert (sg[K * lo // 32: K * hi // 32].reshape(K, (hi - lo) // 32) == ws).all()
+
+
+def test_ragged_splits_without_padding():
+    # any T_e: expert e's nibbles [K, ceil(T_e/2)] and scales [K, ceil(T_e/32)] follow those of the experts
+    # before it; a last block of fewer than 32 rows is quantized over the rows it has
+    K = 128
+    off = np.array([0, 5, 5, 37, 101, 132, 133, 197], np.int32)           # T = 5 0 32 64 31 1 64
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=27, scale_center=120, scale_spread=6)
+    q, sf = q.numpy(), sf.numpy()
+    sf[110, 2] = 0xFF                                                     # NaN inside a partial block
+    qc, sc = ref.row_to_col_grouped(q, sf, off)
+    nib = unpack_nibbles(q)
+    pb = bb = 0
+    for e in range(len(off) - 1):
+        lo, hi = int(off[e]), int(off[e + 1])
+        T = hi - lo
+        if T == 0:
+            continue
+        P, B = (T + 1) // 2, (T + 31) // 32
+        got_q = qc[K * pb:K * (pb + P)].reshape(K, P)
+        got_s = sc[K * bb:K * (bb + B)].reshape(K, B)
+        # (a) the same rows padded with zero rows to a multiple of 32, through the flat function
+        pad = B * 32 - T
+        qp = np.concatenate([q[lo:hi], np.zeros((pad, K // 2), np.uint8)])
+        sp = np.concatenate([sf[lo:hi], np.full((pad, K // 32), 200, np.uint8)])      # zero codes: byte irrelevant
+        wq, ws = ref.row_to_col(qp, sp)
+        assert (got_s == ws).all(), e
+        codes = unpack_nibbles(wq)[:, :T]                                  # [K, T] nibble codes of the real rows
+        want = np.zeros((K, 2 * P), np.uint8)
+        want[:, :T] = codes
+        assert (got_q == (want[:, 0::2] | (want[:, 1::2] << 4))).all(), e
+        # (b) exact rationals on the partial last block of a few columns
+        n_last = T - (B - 1) * 32
+        rows = slice(lo + (B - 1) * 32, hi)
+        for k in (0, 45, 70, K - 1):
+            bytes_ = [int(b) for b in sf[rows, k // 32]]
+            if 0xFF in bytes_:
+                assert got_s[k, B - 1] == 0xFF
+                continue
+            vals = [((int(n) >> 3) & 1, bf.E2M1_GRID[int(n) & 7] * bf.pow2(b - 127)) for n, b in zip(nib[rows, k], bytes_)]
+            vals += [(0, bf.Fraction(0))] * (32 - n_last)
+            b_want, c_want = bf.quant_block(vals)
+            assert got_s[k, B - 1] == b_want
+            got_codes = unpack_nibbles(got_q[k:k + 1])[0, (B - 1) * 32:(B - 1) * 32 + n_last]
+            assert got_codes.tolist() == c_want[:n_last]
+        pb += P
+        bb += B
+    assert qc.size == K * pb and sc.size == K * bb
