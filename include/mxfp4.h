@@ -119,13 +119,17 @@ mxfp4_status mxfp4_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64
 
 /* Ragged per-expert forms (paper sec. 3.4, native support for ragged MoE tensors).
  *   expert_offsets  int32 [num_experts + 1] on the DEVICE: rows [off_e, off_{e+1}) belong to
- *                   expert e; off_0 = 0, off_E = M_total, non-decreasing, every
- *                   T_e = off_{e+1} - off_e a multiple of 32 (T_e = 0 allowed).
+ *                   expert e; off_0 = 0, off_E = M_total, non-decreasing; every
+ *                   T_e = off_{e+1} - off_e may be ANY length >= 0 (no padding needed).
  * Quantization is row-independent, so the grouped form produces exactly what the flat form
  * produces on M_total rows (dense outputs).
- * Grouped row->column writes expert e as its own dense [K, T_e/2] and [K, T_e/32] matrices
- * at byte offsets K*off_e/2 and K*off_e/32 of q_col / sf_col: contiguous storage without
- * padding.  No column block crosses an expert boundary. */
+ * Grouped row->column writes expert e as its own dense [K, ceil(T_e/2)] and [K, ceil(T_e/32)]
+ * matrices at byte offsets K * sum_{j<e} ceil(T_j/2) of q_col and K * sum_{j<e} ceil(T_j/32) of
+ * sf_col (= K*off_e/2 and K*off_e/32 when every T_e is a multiple of 32): contiguous storage
+ * without padding.  No column block crosses an expert boundary; a last block of fewer than 32
+ * rows is quantized over the rows it has, and with an odd T_e the unused high nibble of each
+ * k-row's last byte is 0.  The buffers hold K * sum_e ceil(T_e/2) <= K * (M_total/2 + num_experts)
+ * and K * sum_e ceil(T_e/32) <= K * (M_total/32 + num_experts) bytes. */
 mxfp4_status mxfp4_quant_from_fp8_grouped(const uint8_t *x, const float *x_scale,
                                           const int32_t *expert_offsets, int32_t num_experts,
                                           int64_t M_total, int64_t K, uint8_t *q, uint8_t *sf,

@@ -188,15 +188,18 @@ def mxfp4_quant_from_fp8_grouped(x, x_scale, expert_offsets, q=None, sf=None, st
 
 
 def mxfp4_row_to_col_grouped(q_row, sf_row, expert_offsets, q_col=None, sf_col=None, stream=None):
-    """Outputs are flat byte buffers: expert e's [K,T_e/2] at K*off_e/2, its [K,T_e/32] at K*off_e/32."""
+    """Outputs are flat byte buffers: expert e's [K,ceil(T_e/2)] at K*sum_{j<e} ceil(T_j/2), its [K,ceil(T_e/32)]
+    at K*sum_{j<e} ceil(T_j/32) (K*off_e/2 and K*off_e/32 for multiples of 32); any T_e.  Buffers allocated here
+    have the upper-bound sizes K*(M//2 + num_experts) and K*(M//32 + num_experts)."""
     _dev(q_row, torch.uint8, "q_row")
     _dev(sf_row, torch.uint8, "sf_row")
     _dev(expert_offsets, torch.int32, "expert_offsets")
     M, K = q_row.shape[0], q_row.shape[1] * 2
+    E = expert_offsets.shape[0] - 1
     if q_col is None:
-        q_col = torch.empty(M * K // 2, dtype=torch.uint8, device=q_row.device)
+        q_col = torch.empty(K * (M // 2 + E), dtype=torch.uint8, device=q_row.device)
     if sf_col is None:
-        sf_col = torch.empty(M * K // 32, dtype=torch.uint8, device=q_row.device)
+        sf_col = torch.empty(K * (M // 32 + E), dtype=torch.uint8, device=q_row.device)
     st = lib().mxfp4_row_to_col_grouped(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(),
                                         expert_offsets.shape[0] - 1, M, K, q_col.data_ptr(), sf_col.data_ptr(),
                                         _stream(stream))

@@ -10,25 +10,6 @@ namespace fp8col {
 
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-// The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.
-__device__ __forceinline__ void store_head_bytes(uint8_t *dst, const u32x4 v, uint32_t n)
-{
-    uint32_t pos = 0; // bytes done
-    if (n & 8u) {
-        *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)v.y << 32) | v.x;
-        pos = 8;
-    }
-    if (n & 4u) {
-        *reinterpret_cast<u32_unaligned *>(dst + pos) = pos ? v.z : v.x;
-        pos += 4;
-    }
-    const uint32_t d = pos == 0u ? v.x : pos == 4u ? v.y : pos == 8u ? v.z : v.w; // the dword still open
-    if (n & 2u)
-        *reinterpret_cast<u16_unaligned *>(dst + pos) = (uint16_t)d;
-    if (n & 1u)
-        dst[pos + (n & 2u)] = (uint8_t)(d >> (8u * (n & 2u)));
-}
-
 // Write one LDS part out: 16 lanes per k-row, 256 contiguous bytes.  The part holds CP columns
 // of every lane: LDS row c'*32 + cg is column 8*cg + first_col + c' of the tile, as 16 slots of
 // 16 bytes, the slot of rows 16*l.. being (l + cg) % 16.  Chunk u*T + tid of the part is row

@@ -97,7 +97,8 @@ static mxfp4_status row_to_col_common(const uint8_t *q_row, const uint8_t *sf_ro
                                       int32_t num_experts, int64_t M, int64_t K, uint8_t *q_col,
                                       uint8_t *sf_col, void *hip_stream)
 {
-    if (M < 0 || K < 0 || K % 128 != 0 || M % 32 != 0)
+    // the flat form has whole column blocks; the splits of the grouped form may have any length
+    if (M < 0 || K < 0 || K % 128 != 0 || (!expert_offsets && M % 32 != 0))
         return MXFP4_ERR_SHAPE;
     if (M == 0 || K == 0)
         return MXFP4_OK;

@@ -138,15 +138,15 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
 // workgroup; every wave evaluates it on its own, 64 experts at a time: one coalesced load of the
 // offsets, a wave prefix sum of the tile counts and a ballot, instead of a serial scan whose
 // every step waits for memory.  On success `tile` becomes the tile index inside the expert, and
-// with UNIT_ROWS != 0 `units_before` the sum of ceil(T_j / UNIT_ROWS) over the experts before
-// it (where its scale groups start when the splits are not padded).
-template <uint32_t TILE_ROWS, uint32_t UNIT_ROWS = 0>
+// for a non-zero UNIT_A / UNIT_B, `a_before` / `b_before` the sum of ceil(T_j / UNIT) over the
+// experts before it (where its outputs start when the splits are not padded).
+template <uint32_t TILE_ROWS, uint32_t UNIT_A = 0, uint32_t UNIT_B = 0>
 __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_experts, uint32_t *tile,
-                                               uint32_t *row_base, uint32_t *rows,
-                                               uint32_t *units_before = nullptr)
+                                               uint32_t *row_base, uint32_t *rows, uint32_t *a_before = nullptr,
+                                               uint32_t *b_before = nullptr)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    uint32_t before = 0, ubefore = 0; // tiles / units of the experts in earlier chunks
+    uint32_t before = 0, abefore = 0, bbefore = 0; // tiles / units of the experts in earlier chunks
     for (int32_t base = 0; base < num_experts; base += 64) {
         const int32_t e = base + (int32_t)lane;
         uint32_t lo = 0, hi = 0;
@@ -155,15 +155,20 @@ __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_e
             hi = (uint32_t)off[e + 1];
         }
         const uint32_t nt = (hi - lo + TILE_ROWS - 1u) / TILE_ROWS;
-        const uint32_t nu = UNIT_ROWS ? (hi - lo + UNIT_ROWS - 1u) / (UNIT_ROWS ? UNIT_ROWS : 1u) : 0u;
-        uint32_t incl = nt, uincl = nu; // inclusive prefix sums over the wave
+        const uint32_t na = UNIT_A ? (hi - lo + UNIT_A - 1u) / (UNIT_A ? UNIT_A : 1u) : 0u;
+        const uint32_t nb = UNIT_B ? (hi - lo + UNIT_B - 1u) / (UNIT_B ? UNIT_B : 1u) : 0u;
+        uint32_t incl = nt, aincl = na, bincl = nb; // inclusive prefix sums over the wave
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
             incl += lane >= (uint32_t)d ? up : 0u;
-            if (UNIT_ROWS) {
-                const uint32_t uup = (uint32_t)__shfl_up((int)uincl, d, 64);
-                uincl += lane >= (uint32_t)d ? uup : 0u;
+            if (UNIT_A) {
+                const uint32_t aup = (uint32_t)__shfl_up((int)aincl, d, 64);
+                aincl += lane >= (uint32_t)d ? aup : 0u;
+            }
+            if (UNIT_B) {
+                const uint32_t bup = (uint32_t)__shfl_up((int)bincl, d, 64);
+                bincl += lane >= (uint32_t)d ? bup : 0u;
             }
         }
         const uint64_t hit = __ballot(before + incl > *tile);
@@ -173,15 +178,38 @@ __device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_e
             *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo, l);
             *rows = (uint32_t)__builtin_amdgcn_readlane((int)(hi - lo), l);
             *tile -= before + excl;
-            if (UNIT_ROWS)
-                *units_before = ubefore + (uint32_t)__builtin_amdgcn_readlane((int)(uincl - nu), l);
+            if (UNIT_A)
+                *a_before = abefore + (uint32_t)__builtin_amdgcn_readlane((int)(aincl - na), l);
+            if (UNIT_B)
+                *b_before = bbefore + (uint32_t)__builtin_amdgcn_readlane((int)(bincl - nb), l);
             return true;
         }
         before += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-        if (UNIT_ROWS)
-            ubefore += (uint32_t)__builtin_amdgcn_readlane((int)uincl, 63);
+        if (UNIT_A)
+            abefore += (uint32_t)__builtin_amdgcn_readlane((int)aincl, 63);
+        if (UNIT_B)
+            bbefore += (uint32_t)__builtin_amdgcn_readlane((int)bincl, 63);
     }
     return false;
+}
+
+// The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.
+__device__ __forceinline__ void store_head_bytes(uint8_t *dst, const u32x4 v, uint32_t n)
+{
+    uint32_t pos = 0; // bytes done
+    if (n & 8u) {
+        *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)v.y << 32) | v.x;
+        pos = 8;
+    }
+    if (n & 4u) {
+        *reinterpret_cast<u32_unaligned *>(dst + pos) = pos ? v.z : v.x;
+        pos += 4;
+    }
+    const uint32_t d = pos == 0u ? v.x : pos == 4u ? v.y : pos == 8u ? v.z : v.w; // the dword still open
+    if (n & 2u)
+        *reinterpret_cast<u16_unaligned *>(dst + pos) = (uint16_t)d;
+    if (n & 1u)
+        dst[pos + (n & 2u)] = (uint8_t)(d >> (8u * (n & 2u)));
 }
 
 // Compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>).

@@ -136,15 +136,16 @@ __device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&s
 // Relative to it, t = 2*(b_row + E - b_col) + M orders the values; t >= 2 are E2M1 normals
 // and stay exact (code t), and below that RTNE gives t = 1 -> 1.0 (tie .75, even code 2),
 // t = 0 and -1 -> 0.5 (code 1), t = -2 -> 0 (tie .25), lower -> 0.
+// Only the first n_valid rows of the slice exist (fewer than 32 at the ragged end of a split).
 __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t src_pitch, const uint8_t *row_sf,
-                                                   uint32_t *out_row0, uint32_t out_row_stride)
+                                                   uint32_t *out_row0, uint32_t out_row_stride, int n_valid)
 {
     uint64_t col_bytes = 0;
 #pragma nounroll
     for (int c = 0; c < 8; ++c) {
         int emax = -1024;
 #pragma nounroll
-        for (int i = 0; i < 32; ++i) {
+        for (int i = 0; i < n_valid; ++i) {
             const uint32_t wi = *reinterpret_cast<const uint32_t *>(src + (size_t)i * src_pitch);
             const int mag = (int)(wi >> (4 * c)) & 7;
             if (mag)
@@ -158,6 +159,8 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
 #pragma nounroll
             for (int i8 = 0; i8 < 8; ++i8) {
                 const int i = g * 8 + i8;
+                if (i >= n_valid)
+                    break; // the nibbles of rows that do not exist stay 0
                 const uint32_t wi = *reinterpret_cast<const uint32_t *>(src + (size_t)i * src_pitch);
                 const uint32_t nib = (wi >> (4 * c)) & 0xFu;
                 const int mag = (int)(nib & 7u);
@@ -192,22 +195,25 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k))
         return;
 
-    // ---- which rows: the whole matrix, or one expert's slice (uniform per workgroup)
-    uint32_t row_base = 0, rows = a.M;
-    if (a.expert_offsets && !tile_of_expert<TILE_M>(a.expert_offsets, a.num_experts, &strip, &row_base, &rows))
+    // ---- which rows: the whole matrix, or one expert's slice of any length (uniform per workgroup)
+    uint32_t row_base = 0, rows = a.M, bytes_before = 0, blocks_before = 0;
+    if (a.expert_offsets && !tile_of_expert<TILE_M, 2, 32>(a.expert_offsets, a.num_experts, &strip, &row_base, &rows,
+                                                           &bytes_before, &blocks_before))
         return;
     const uint32_t m0 = strip * TILE_M;
     if (m0 >= rows)
         return;
-    const uint32_t n_rg = min((uint32_t)TILE_M, rows - m0) / 32u; // row groups present
+    const uint32_t n_rows = min((uint32_t)TILE_M, rows - m0); // rows present: 1..256
+    const uint32_t n_rg = (n_rows + 31u) / 32u;               // row groups present, the last maybe partial
     const uint32_t k0 = tile_k * TILE_K;
     const uint32_t cols = min((uint32_t)TILE_K, a.K - k0); // 128 or 256
     const uint32_t Kb = a.K / 32u;
 
-    // expert e's output is its own dense [K, rows/2] and [K, rows/32]
-    uint8_t *out_q = a.q_col + (size_t)a.K * row_base / 2;
-    uint8_t *out_sf = a.sf_col + (size_t)a.K * row_base / 32;
-    const size_t pitch_q = rows / 2, pitch_sf = rows / 32;
+    // expert e's output is its own dense [K, ceil(rows/2)] and [K, ceil(rows/32)], after those of
+    // the experts before it
+    uint8_t *out_q = a.q_col + (size_t)a.K * bytes_before;
+    uint8_t *out_sf = a.sf_col + (size_t)a.K * blocks_before;
+    const size_t pitch_q = (rows + 1u) / 2u, pitch_sf = (rows + 31u) / 32u;
 
     const uint32_t tid = threadIdx.x;
     const uint32_t rg = tid >> 5, cg = tid & 31u;
@@ -216,13 +222,13 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     // consecutive lanes write different banks and the read-back is linear
     const uint32_t slot = (rg + (cg >> 1)) & (NRG - 1u);
     const uint32_t lane_off = rg * 32u * pitch + cg * 4u;
-    const bool active = rg < n_rg && cg * 8u < cols;
+    const bool active = rg * 32u < n_rows && cg * 8u < cols;
 
     // the tile's row scales: thread t takes row t, one 8-byte request where the layout allows it
     // (K % 256 == 0), else 4 + 4
     uint32_t lo = 0, hi = 0;
     auto load_sf = [&]() {
-        if (tid < n_rg * 32u) {
+        if (tid < n_rows) {
             const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
             if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
                 const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
@@ -240,10 +246,21 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     auto load_slice = [&]() {
         if (active) {
             const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
+            if (n_rows == (uint32_t)TILE_M) {
 #pragma unroll
-            for (int i = 0; i < 32; ++i)
-                w[i] = __builtin_nontemporal_load(
-                    reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+                for (int i = 0; i < 32; ++i)
+                    w[i] = __builtin_nontemporal_load(
+                        reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+            } else {
+                // ragged end of a split: rows past it count as zeros (read from the last row, then cleared)
+                const uint32_t last = n_rows - 1u - rg * 32u;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    const uint32_t v = __builtin_nontemporal_load(
+                        reinterpret_cast<const uint32_t *>(tile_src + lane_off + min((uint32_t)i, last) * pitch));
+                    w[i] = (uint32_t)i <= last ? v : 0u;
+                }
+            }
         }
     };
     load_slice();
@@ -251,7 +268,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     // ---- stage the row scales.  A wave stages two row groups; one ballot per k-block tells which
     // (row group, k-block) pairs hold a byte of 253 or more (beyond FP32, or NaN).
     {
-        if (tid < n_rg * 32u) {
+        if (tid < TILE_M) { // rows that do not exist are staged as byte 0
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
@@ -310,7 +327,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             } else {
                 const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
                 col_bytes = requant_slice_int(tile_src + lane_off, pitch, my_row_sf,
-                                              reinterpret_cast<uint32_t *>(&s_out[cg * NRG + slot]), 32 * NRG * 4);
+                                              reinterpret_cast<uint32_t *>(&s_out[cg * NRG + slot]), 32 * NRG * 4,
+                                              (int)min(32u, n_rows - rg * 32u));
             }
         }
 #pragma unroll
@@ -340,10 +358,24 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         const uint32_t cgx = tid / NRG;
         const uint32_t part = ((tid & (NRG - 1u)) - (cgx >> 1)) & (NRG - 1u);
         uint8_t *dst = out_q + (size_t)(k0 + cgx * 8u) * pitch_q + m0 / 2u + part * 16u;
-        if (cgx * 8u < cols && part < n_rg) {
+        // bytes of this lane's 16 (= 32 rows) that exist: fewer at the ragged end of a split, where
+        // k-rows also start at any byte (global memory takes unaligned vector stores)
+        const uint32_t have = part * 32u < n_rows ? min(16u, (n_rows - part * 32u + 1u) / 2u) : 0u;
+        const bool aligned16 = ((reinterpret_cast<uintptr_t>(out_q) | pitch_q) & 15u) == 0u;
+        if (cgx * 8u < cols && have != 0u) {
+            if (have == 16u && aligned16) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
+                for (int u = 0; u < 8; ++u)
+                    *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
+            } else if (have == 16u) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    *reinterpret_cast<u32x4_unaligned *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
+            } else {
+#pragma nounroll
+                for (int u = 0; u < 8; ++u)
+                    store_head_bytes(dst + (size_t)u * pitch_q, s_out[u * T_THREADS + tid], have);
+            }
         }
     }
 }

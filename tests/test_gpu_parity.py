@@ -183,8 +183,8 @@ def test_grouped_variants_small():
     assert_same(host(sf), wsf, "grouped quant scales")
     qc, sc = mx.mxfp4_row_to_col_grouped(dev(wq), dev(wsf), off.to(DEV))
     wqc, wsc = ref.row_to_col_grouped(wq, wsf, off.numpy())
-    assert_same(host(sc), wsc, "grouped row->col scales")
-    assert_same(host(qc), wqc, "grouped row->col nibbles")
+    assert_same(host(sc)[:wsc.size], wsc, "grouped row->col scales")
+    assert_same(host(qc)[:wqc.size], wqc, "grouped row->col nibbles")
 
 
 def test_grouped_with_empty_experts():
@@ -193,8 +193,8 @@ def test_grouped_with_empty_experts():
     q, sf = q.numpy(), sf.numpy()
     qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), off.to(DEV))
     wqc, wsc = ref.row_to_col_grouped(q, sf, off.numpy())
-    assert_same(host(sc), wsc, "grouped row->col scales")
-    assert_same(host(qc), wqc, "grouped row->col nibbles")
+    assert_same(host(sc)[:wsc.size], wsc, "grouped row->col scales")
+    assert_same(host(qc)[:wqc.size], wqc, "grouped row->col nibbles")
 
 
 def test_gather_and_token_records():
@@ -384,8 +384,8 @@ def test_grouped_more_experts_than_a_wave():
     offd = torch.from_numpy(off).to(DEV)
     qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd)
     wqc, wsc = ref.row_to_col_grouped(q, sf, off)
-    assert_same(host(sc), wsc, "150 experts row->col scales")
-    assert_same(host(qc), wqc, "150 experts row->col nibbles")
+    assert_same(host(sc)[:wsc.size], wsc, "150 experts row->col scales")
+    assert_same(host(qc)[:wqc.size], wqc, "150 experts row->col nibbles")
     x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd)
     wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off)
     assert_same(host(xs)[:wxs.size], wxs, "150 experts row->FP8 col scales")
@@ -559,3 +559,25 @@ def test_side_stream_and_graph_replays():
         for got, want, name in ((q, wq, "q"), (sf, wsf, "sf"), (xb, wx, "x"), (sb, wxs, "x_scale"), (qc, wqc, "q_col"),
                                 (sc, wsc, "sf_col"), (xc, wxc, "x_col"), (xcs, wxcs, "x_col_scale")):
             assert_same(host(got), want, f"graph replay: {name}")
+
+
+@pytest.mark.parametrize("K", [256, 384])
+def test_row_to_col_ragged_splits_without_padding(K):
+    # any T_e: partial last blocks, partial tiles, odd lengths, unaligned k-rows; guard bytes around the outputs
+    T = [5, 0, 32, 256, 31, 257, 1, 300, 16, 15, 17, 511, 0, 130, 33] + [0] * 60 + [64, 3]
+    off = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=51 + K, scale_center=120, scale_spread=8, nan_scale_frac=0.002)
+    q, sf = q.numpy(), sf.numpy()
+    sf[40:44, 0] = 254                                                    # beyond FP32 inside a partial tile
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off)
+    guard = 4096
+    qbuf = torch.full((guard + wqc.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    sbuf = torch.full((guard + wsc.size + guard,), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV), q_col=qbuf[guard:guard + wqc.size],
+                                sf_col=sbuf[guard:guard + wsc.size])
+    qb, sb = host(qbuf), host(sbuf)
+    assert (qb[:guard] == 0xA5).all() and (qb[guard + wqc.size:] == 0xA5).all(), "bytes written outside q_col"
+    assert (sb[:guard] == 0x5A).all() and (sb[guard + wsc.size:] == 0x5A).all(), "bytes written outside sf_col"
+    assert_same(sb[guard:guard + wsc.size], wsc, "ragged row->col: column scales")
+    assert_same(qb[guard:guard + wqc.size], wqc, "ragged row->col: nibbles")
