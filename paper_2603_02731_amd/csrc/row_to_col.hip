@@ -42,6 +42,10 @@ constexpr int NRG = MXFP4_RTC_NRG;  // 32-row groups per tile
 constexpr int T_THREADS = 32 * NRG; // one lane per (row group, 8-column group)
 constexpr int TILE_M = 32 * NRG;
 constexpr int TILE_K = 256;
+#ifndef MXFP4_RTC_SFPAD
+#define MXFP4_RTC_SFPAD 16
+#endif
+constexpr int SF_STRIDE = TILE_M + MXFP4_RTC_SFPAD; // row scales of one k-block in LDS; the pad spreads the k-blocks over the banks
 static_assert(NRG == 8, "the LDS slot swizzle and the copy-out assume 8 row groups");
 
 struct RowToColArgs {
@@ -187,7 +191,7 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
 __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
 {
     __shared__ u32x4 s_out[TILE_K * NRG];                // [c*32 + cg][slot]: 256 k-rows x 128 B
-    __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
+    __shared__ alignas(16) uint8_t s_row_sf[8 * SF_STRIDE]; // [k-block of the tile][row]
     __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [k][row group]
     __shared__ uint8_t s_special[NRG];                   // per row group: bit kb set = a scale byte >= 253
 
@@ -271,8 +275,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         if (tid < TILE_M) { // rows that do not exist are staged as byte 0
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                s_row_sf[j * TILE_M + tid] = (uint8_t)(lo >> (8 * j));
-                s_row_sf[(4 + j) * TILE_M + tid] = (uint8_t)(hi >> (8 * j));
+                s_row_sf[j * SF_STRIDE + tid] = (uint8_t)(lo >> (8 * j));
+                s_row_sf[(4 + j) * SF_STRIDE + tid] = (uint8_t)(hi >> (8 * j));
             }
         }
         uint32_t special_lo = 0, special_hi = 0;
@@ -291,7 +295,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     __syncthreads();
 
     if (active) {
-        const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * TILE_M + rg * 32u];
+        const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * SF_STRIDE + rg * 32u];
         uint64_t col_bytes;
         if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
             uint32_t sb[8];
@@ -333,15 +337,16 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         }
 #pragma unroll
         for (int c = 0; c < 8; ++c)
-            s_col_sf[(cg * 8 + c) * NRG + rg] = (uint8_t)(col_bytes >> (8 * c));
+            s_col_sf[(c * 32 + cg) * NRG + rg] = (uint8_t)(col_bytes >> (8 * c));
     }
     __syncthreads();
 
     // ---- out: the column scales as one request per k-row, then the nibbles, 8 lanes per k-row with
     // 128 contiguous bytes each.  Chunk u*256 + tid of the LDS tile is row (u*32 + tid/8), slot
     // tid%8: column k = (tid/8)*8 + u.  Both read LDS regions written before the one barrier above.
-    if (tid < cols) {
-        uint8_t *dst = out_sf + (size_t)(k0 + tid) * pitch_sf + m0 / 32u;
+    const uint32_t sf_k = (tid & 31u) * 8u + (tid >> 5); // slot tid of the staged column scales is column sf_k
+    if (sf_k < cols) {
+        uint8_t *dst = out_sf + (size_t)(k0 + sf_k) * pitch_sf + m0 / 32u;
         const uint8_t *src = &s_col_sf[tid * NRG];
         const uintptr_t al = reinterpret_cast<uintptr_t>(dst);
         if (n_rg == 8u && (al & 7u) == 0u) {
