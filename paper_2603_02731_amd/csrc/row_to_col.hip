@@ -45,7 +45,8 @@ constexpr int TILE_K = 256;
 #ifndef MXFP4_RTC_SFPAD
 #define MXFP4_RTC_SFPAD 16
 #endif
-constexpr int SF_STRIDE = TILE_M + MXFP4_RTC_SFPAD; // row scales of one k-block in LDS; the pad spreads the k-blocks over the banks
+// row scales of one k-block in LDS; the pad spreads the k-blocks over the banks
+constexpr int SF_STRIDE = TILE_M + MXFP4_RTC_SFPAD;
 static_assert(NRG == 8, "the LDS slot swizzle and the copy-out assume 8 row groups");
 
 struct RowToColArgs {
@@ -192,7 +193,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
 {
     __shared__ u32x4 s_out[TILE_K * NRG];                // [c*32 + cg][slot]: 256 k-rows x 128 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * SF_STRIDE]; // [k-block of the tile][row]
-    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [k][row group]
+    __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [slot c*32 + cg of column cg*8 + c][row group]
     __shared__ uint8_t s_special[NRG];                   // per row group: bit kb set = a scale byte >= 253
 
     uint32_t strip, tile_k;
