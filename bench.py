@@ -299,6 +299,15 @@ def time_variants(torch, mx, synth, x8, s, q, sf, a, iters=10):
         scc = torch.empty(Mt * K // 32, dtype=torch.uint8, device=dev)
         us = timed(lambda: mx.mxfp4_row_to_col_grouped(q[:Mt], sf[:Mt], offd, q_col=qc, sf_col=scc))
         res["row_to_col_grouped_32_experts"] = entry(us, Mt * K * BYTES_PER_ELEM["row_to_col"], rows=Mt)
+    if want("row_to_col_ragged_32_experts"):
+        # the same expert counts without padding: arbitrary T_e, partial last blocks, k-rows at any byte
+        offr, _ = synth.expert_offsets(seed=a.seed, num_experts=32, total_tokens=M - 32 * 128, pad_to=1)
+        Mr = int(offr[-1])
+        offrd = offr.to(dev)
+        qcr = torch.empty(Mr * K // 2 + 32 * K, dtype=torch.uint8, device=dev)
+        scr = torch.empty(Mr * K // 32 + 32 * K, dtype=torch.uint8, device=dev)
+        us = timed(lambda: mx.mxfp4_row_to_col_grouped(q[:Mr], sf[:Mr], offrd, q_col=qcr, sf_col=scr))
+        res["row_to_col_ragged_32_experts"] = entry(us, Mr * K * BYTES_PER_ELEM["row_to_col"], rows=Mr)
     return res
 
 

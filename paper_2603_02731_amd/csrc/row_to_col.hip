@@ -348,17 +348,13 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     const uint32_t sf_k = (tid & 31u) * 8u + (tid >> 5); // slot tid of the staged column scales is column sf_k
     if (sf_k < cols) {
         uint8_t *dst = out_sf + (size_t)(k0 + sf_k) * pitch_sf + m0 / 32u;
-        const uint8_t *src = &s_col_sf[tid * NRG];
-        const uintptr_t al = reinterpret_cast<uintptr_t>(dst);
-        if (n_rg == 8u && (al & 7u) == 0u) {
-            *reinterpret_cast<u32x2 *>(dst) = *reinterpret_cast<const u32x2 *>(src);
-        } else if ((n_rg & 3u) == 0u && (al & 3u) == 0u) {
-            for (uint32_t g = 0; g < n_rg; g += 4u)
-                *reinterpret_cast<uint32_t *>(dst + g) = *reinterpret_cast<const uint32_t *>(src + g);
-        } else {
-            for (uint32_t g = 0; g < n_rg; ++g)
-                dst[g] = src[g];
-        }
+        const u32x2 v = *reinterpret_cast<const u32x2 *>(&s_col_sf[tid * NRG]);
+        // one request per k-row at any alignment (the pitch of an expert's scale rows is any number of
+        // bytes): 8 bytes for a full tile, the pieces of store_head_bytes for a tile that ends early
+        if (n_rg == 8u)
+            *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)v.y << 32) | v.x;
+        else
+            store_head_bytes(dst, u32x4{v.x, v.y, 0u, 0u}, n_rg);
     }
     {
         const uint32_t cgx = tid / NRG;
