@@ -222,14 +222,11 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
                 bits[gg] = 0x7FC00000u;
         }
         float *dst = out_s + (size_t)(k0 + tid) * pitch_s + m0 / 128u;
-        if (n_g == 2u && (reinterpret_cast<uintptr_t>(dst) & 7u) == 0u) {
-            *reinterpret_cast<u32x2 *>(dst) = u32x2{bits[0], bits[1]};
-        } else {
-            if (n_g >= 1u)
-                dst[0] = u2f(bits[0]);
-            if (n_g == 2u)
-                dst[1] = u2f(bits[1]);
-        }
+        // one request per k-row: an expert's scale rows start at any multiple of 4 bytes
+        if (n_g == 2u)
+            *reinterpret_cast<u64_unaligned *>(dst) = ((uint64_t)bits[1] << 32) | bits[0];
+        else if (n_g == 1u)
+            dst[0] = u2f(bits[0]);
     }
 
     // ---- the row-scale bytes of this slice (byte i%4 of dword i/4 is row i) -> decode operands
