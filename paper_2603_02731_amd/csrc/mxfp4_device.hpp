@@ -26,6 +26,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // The same through pointers of any alignment (global memory takes unaligned vector accesses).
 typedef u32x4 __attribute__((aligned(1))) u32x4_unaligned;
+typedef u32x2 __attribute__((aligned(1))) u32x2_unaligned;
 typedef uint64_t __attribute__((aligned(1))) u64_unaligned;
 typedef uint32_t __attribute__((aligned(1))) u32_unaligned;
 typedef uint16_t __attribute__((aligned(1))) u16_unaligned;

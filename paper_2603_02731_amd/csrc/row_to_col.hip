@@ -229,19 +229,18 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     const uint32_t lane_off = rg * 32u * pitch + cg * 4u;
     const bool active = rg * 32u < n_rows && cg * 8u < cols;
 
-    // the tile's row scales: thread t takes row t, one 8-byte request where the layout allows it
-    // (K % 256 == 0), else 4 + 4
+    // the tile's row scales: thread t takes row t, one 8-byte request (4 bytes for a 128-column tile)
     uint32_t lo = 0, hi = 0;
     auto load_sf = [&]() {
         if (tid < n_rows) {
             const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
-            if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
-                const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+            if (cols > 128u) { // one request at any 4-byte alignment
+                const u32x2 v = *reinterpret_cast<const u32x2_unaligned *>(p);
                 lo = v.x;
                 hi = v.y;
             } else {
                 lo = reinterpret_cast<const uint32_t *>(p)[0];
-                hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
+                hi = 0u;
             }
         }
     };

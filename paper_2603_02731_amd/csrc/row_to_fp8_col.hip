@@ -166,13 +166,12 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         if (row < n_rows) {
             const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + row) * Kb + k0 / 32u;
             if (PARTS == 1) {
-                if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
-                    const u32x2 t = *reinterpret_cast<const u32x2 *>(p);
+                if (cols > 128u) { // one request at any 4-byte alignment
+                    const u32x2 t = *reinterpret_cast<const u32x2_unaligned *>(p);
                     v[0] = t.x;
                     v[1] = t.y;
                 } else {
                     v[0] = reinterpret_cast<const uint32_t *>(p)[0];
-                    v[1] = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
                 }
             } else if (part == 0u || cols > 128u) {
                 v[0] = reinterpret_cast<const uint32_t *>(p)[part];

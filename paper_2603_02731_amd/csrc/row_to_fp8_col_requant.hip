@@ -181,13 +181,12 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
         uint32_t lo = 0, hi = 0;
         if (tid < n_rows) {
             const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + tid) * Kb + k0 / 32u;
-            if (cols > 128u && (reinterpret_cast<uintptr_t>(p) & 7u) == 0u) {
-                const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+            if (cols > 128u) { // one request at any 4-byte alignment
+                const u32x2 v = *reinterpret_cast<const u32x2_unaligned *>(p);
                 lo = v.x;
                 hi = v.y;
             } else {
                 lo = reinterpret_cast<const uint32_t *>(p)[0];
-                hi = cols > 128u ? reinterpret_cast<const uint32_t *>(p)[1] : 0u;
             }
         }
         uint32_t special = 0;
