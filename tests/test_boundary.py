@@ -73,3 +73,24 @@ def test_argument_validation_without_a_gpu():
     assert L.mxfp4_row_to_col(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col_grouped(a16, a16, a16, 1025, 128, 128, a16, a16, None) == binding.ERR_OFFSETS
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU: bench.py --gpus N with N > 1 exits with a message and touches no GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2", "--steps", "1"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_nothing_in_the_product_path_touches_the_oracle():
+    """oracle/ is test infrastructure: the package and the kernels never import, link or read it."""
+    pkg = os.path.join(ROOT, "paper_2603_02731_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "mxfp4_ref" not in text, f"{f} names the oracle's library"
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f"{f} imports the oracle"
