@@ -64,6 +64,19 @@ struct RowToColArgs {
 
 constexpr uint32_t MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK; // macro block of the tile order
 
+// The nibbles are read once: non-temporal loads (plain loads: 109 us against 94 at [65536,7168]).
+#ifndef MXFP4_RTC_NT_LOAD
+#define MXFP4_RTC_NT_LOAD 1
+#endif
+__device__ __forceinline__ uint32_t load_nibbles(const uint32_t *p)
+{
+#if MXFP4_RTC_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 // One lane's 32x8 slice through the hardware conversions.  Exact while every value
 // e2m1 * 2^(b-127) is an FP32 number, i.e. for row-scale bytes up to 252
 // (6 * 2^125 < 2^128; the smallest, 0.5 * 2^-127, is an FP32 subnormal).
@@ -253,15 +266,14 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             if (n_rows == (uint32_t)TILE_M) {
 #pragma unroll
                 for (int i = 0; i < 32; ++i)
-                    w[i] = __builtin_nontemporal_load(
-                        reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
+                    w[i] = load_nibbles(reinterpret_cast<const uint32_t *>(tile_src + (size_t)i * pitch + lane_off));
             } else {
                 // ragged end of a split: rows past it count as zeros (read from the last row, then cleared)
                 const uint32_t last = n_rows - 1u - rg * 32u;
 #pragma unroll
                 for (int i = 0; i < 32; ++i) {
-                    const uint32_t v = __builtin_nontemporal_load(
-                        reinterpret_cast<const uint32_t *>(tile_src + lane_off + min((uint32_t)i, last) * pitch));
+                    const uint32_t v =
+                        load_nibbles(reinterpret_cast<const uint32_t *>(tile_src + lane_off + min((uint32_t)i, last) * pitch));
                     w[i] = (uint32_t)i <= last ? v : 0u;
                 }
             }
