@@ -22,8 +22,8 @@ BYTES_PER_ELEM = {"quant": 1.03125 + 0.53125, "dequant": 0.53125 + 1.03125, "row
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
-    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--rows", type=int, default=65536, help="M of the workload (tokens)")
     p.add_argument("--hidden", type=int, default=7168, help="K of the workload")
     p.add_argument("--seed", type=int, default=0)
