@@ -1,0 +1,112 @@
+"""GPU parity on seeded random shapes: every entry point against the CPU oracle, bit for bit, on
+shapes and expert splits that no other test fixes by hand (tiles of 128 and 256 columns, partial
+row tiles, odd split lengths, empty experts, unaligned k-rows), with guard bytes around every
+output of the ragged forms."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_02731_amd as mx
+from oracle import ref
+from paper_2603_02731_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+GUARD = 1024
+
+
+def dev(a):
+    return torch.as_tensor(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def same(got, want, what):
+    got, want = np.asarray(got).reshape(-1), np.asarray(want).reshape(-1)
+    assert got.size == want.size, (what, got.size, want.size)
+    if got.dtype == np.float32:
+        got, want = got.view(np.uint32), want.view(np.uint32)
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"{what}: {bad.size} mismatches, first at {int(bad[0])}"
+
+
+def guarded(n, dtype, fill):
+    buf = torch.full((GUARD + n + GUARD,), fill, dtype=dtype, device=DEV)
+    return buf, buf[GUARD:GUARD + n]
+
+
+def check_guards(buf, n, fill, what):
+    b = host(buf)
+    assert (b[:GUARD] == fill).all() and (b[GUARD + n:] == fill).all(), f"{what}: written outside the output"
+    return b[GUARD:GUARD + n]
+
+
+def random_splits(rng, total_cap):
+    """Expert lengths of every kind: empty, shorter than a block, odd, multiples of 32/128/256, long."""
+    kinds = [0, 1, 5, 31, 32, 33, 64, 96, 127, 128, 129, 255, 256, 257, 300, 384, 511, 513]
+    n = int(rng.integers(1, 12))
+    T = [int(rng.choice(kinds)) for _ in range(n)]
+    while sum(T) > total_cap:
+        T.pop()
+    if sum(T) == 0:
+        T.append(32)
+    return T
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_flat_entry_points_on_random_shapes(seed):
+    rng = np.random.default_rng(1000 + seed)
+    M = 32 * int(rng.integers(1, 40))            # row->col needs M % 32 == 0
+    K = 128 * int(rng.integers(1, 9))
+    x8, s = synth.fp8_blockwise_quantize(torch.from_numpy(
+        (rng.standard_t(3, size=(M, K)) * 10.0 ** rng.uniform(-3, 3)).astype(np.float32)))
+    x8, s = x8.numpy(), s.numpy()
+    q, sf = mx.mxfp4_quant_from_fp8(dev(x8), dev(s))
+    wq, wsf = ref.quant_from_fp8(x8, s)
+    same(host(sf), wsf, f"quant scales [{M},{K}]")
+    same(host(q), wq, f"quant nibbles [{M},{K}]")
+    x, xs = mx.mxfp4_dequant_to_fp8(q, sf)
+    wx, wxs = ref.dequant_to_fp8(wq, wsf)
+    same(host(xs), wxs, f"dequant scales [{M},{K}]")
+    same(host(x), wx, f"dequant bytes [{M},{K}]")
+    qc, sc = mx.mxfp4_row_to_col(q, sf)
+    wqc, wsc = ref.row_to_col(wq, wsf)
+    same(host(sc), wsc, f"row->col scales [{M},{K}]")
+    same(host(qc), wqc, f"row->col nibbles [{M},{K}]")
+    if M % 128 == 0:
+        for requant in (False, True):
+            xc, xcs = mx.mxfp4_row_to_fp8_col(q, sf, requant=requant)
+            wxc, wxcs = ref.row_to_fp8_col(wq, wsf, requant=requant)
+            same(host(xcs), wxcs, f"row->FP8 col scales [{M},{K}] requant={requant}")
+            same(host(xc), wxc, f"row->FP8 col bytes [{M},{K}] requant={requant}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_grouped_entry_points_on_random_splits(seed):
+    rng = np.random.default_rng(2000 + seed)
+    K = 128 * int(rng.integers(1, 7))
+    T = random_splits(rng, 2400)
+    off = np.concatenate([[0], np.cumsum(T)]).astype(np.int32)
+    M = int(off[-1])
+    q, sf = synth.random_mxfp4(M, K, seed=3000 + seed, scale_center=int(rng.integers(60, 200)),
+                               scale_spread=int(rng.integers(0, 12)), nan_scale_frac=0.002 * (seed % 3))
+    q, sf = q.numpy(), sf.numpy()
+    offd = torch.from_numpy(off).to(DEV)
+
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off)
+    qbuf, qv = guarded(wqc.size, torch.uint8, 0xA5)
+    sbuf, sv = guarded(wsc.size, torch.uint8, 0x5A)
+    mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd, q_col=qv, sf_col=sv)
+    same(check_guards(sbuf, wsc.size, 0x5A, "sf_col"), wsc, f"grouped row->col scales T={T} K={K}")
+    same(check_guards(qbuf, wqc.size, 0xA5, "q_col"), wqc, f"grouped row->col nibbles T={T} K={K}")
+
+    for requant in (False, True):
+        wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off, requant=requant)
+        xbuf, xv = guarded(wx.size, torch.uint8, 0xA5)
+        fbuf, fv = guarded(wxs.size, torch.float32, -7.0)
+        mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, x_col=xv, x_col_scale=fv, requant=requant)
+        same(check_guards(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"grouped FP8 col scales T={T} K={K} requant={requant}")
+        same(check_guards(xbuf, wx.size, 0xA5, "x_col"), wx, f"grouped FP8 col bytes T={T} K={K} requant={requant}")
