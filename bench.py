@@ -171,6 +171,7 @@ def main():
     copy_gbps = 2 * n * 20 / (c0.elapsed_time(c1) * 1e-3) * 1e-9
     for name in names:
         kernels[name]["frac_of_measured_copy"] = kernels[name]["GB/s"] / copy_gbps
+        kernels[name]["traffic"] = measured_traffic(name, M, K)  # HBM bytes per launch by rocprofv3 counters
     dom = max(names, key=lambda k: kernels[k]["us"])
     traffic = measured_traffic(dom, M, K)
 
