@@ -202,6 +202,25 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
 // overlap worse than the saved requests gain), 512-row tiles (100 us, with or without
 // non-temporal stores), non-temporal stores for the 128-byte output rows (97 us), requesting the
 // row scales before the nibbles (no difference).
+// The scale bytes sit in LDS so that no access piles up on one bank: the k-blocks of the row
+// scales are SF_STRIDE = 272 bytes apart (the eight 32-byte reads of a wave fall on different
+// banks), and the byte of column cg*8 + c goes to slot c*32 + cg, which lane tid reads back
+// linearly (94-95 -> 92-93 us; with slot k = cg*8 + c the eight byte writes of a lane met
+// 16-way conflicts, 70 % of the kernel's LDS cycles).
+// A tile copy with the same loads, stores and LDS traffic but no arithmetic takes 88 us, and 81 us
+// when the nibbles arrive through 16-byte loads.  No form of wider loads paid here, each measured
+// bit-identical to this kernel and against it in the same run (89.7 us launched back to back):
+// 16-byte loads straight into LDS (global_load_lds_dwordx4, extra barrier, 32 LDS reads per lane:
+// 89.1 us), through registers into LDS (87.5 us at this shape, but 6 % slower at [16384,2048] and
+// [4096,7168] and no faster at [262144,2048]), a lane owning 8 rows x 32 columns and combining the
+// column maxima across four lanes (v_permlane16_swap, row_ror:8; 87.7 us alone, no gain inside the
+// step), 8-byte loads with the lanes of a pair on alternate rows and a DPP exchange of the halves
+// (98 us: adjacent lanes on different rows coalesce badly).  Nor did workgroups that stay resident
+// and walk several k-tiles with the next tile's loads in flight during the conversion (3 or 4 per
+// CU, 100-104 us): the loads only enter the memory pipeline as fast as it drains, so a wave that
+// issues them early waits at the issue instead.  Storing 8 consecutive k-rows per instruction
+// instead of every 8th: 93 us.  Macro blocks of 8/16/64/128 row tiles: 95-109 us (32 = the CUs of
+// an XCD); the kernel without its arithmetic: 89.4 us.
 __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
 {
     __shared__ u32x4 s_out[TILE_K * NRG];                // [c*32 + cg][slot]: 256 k-rows x 128 B
