@@ -31,6 +31,15 @@ constexpr int QUANT_UNROLL = MXFP4_QUANT_UNROLL;
 #define MXFP4_QUANT_NT_STORE 0
 #endif
 
+// Gathered form (top-8 payload of 65536 tokens), policies fixed at compile time per kernel instance: plain loads
+// with non-temporal stores 1012 us, plain loads with plain stores 1090 us, non-temporal loads with plain
+// stores 1130 us.
+#ifndef MXFP4_GATHER_NT_LOAD
+#define MXFP4_GATHER_NT_LOAD 0
+#endif
+#ifndef MXFP4_GATHER_NT_STORE
+#define MXFP4_GATHER_NT_STORE 1
+#endif
 // Scatter form: non-temporal stores of the packed rows 463 us at 65536 tokens x top-8, plain stores 645 us.
 #ifndef MXFP4_SCATTER_NT_STORE
 #define MXFP4_SCATTER_NT_STORE 1
@@ -93,7 +102,7 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
 // `tid` of each run, so every load and store instruction of a wave stays contiguous
 // (1 KiB in, 512 B out) while each lane keeps QUANT_UNROLL loads in flight.
 // DENSE: no gather and dense outputs -- every address is a multiple of the flat chunk index.
-template <bool DENSE>
+template <bool DENSE, bool GATHER>
 __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const QuantArgs a)
 {
     const uint32_t c0 = blockIdx.x * (QUANT_THREADS * QUANT_UNROLL) + threadIdx.x;
@@ -119,7 +128,7 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
             const uint32_t row = c / a.chunks_per_row;
             const uint32_t cc = c - row * a.chunks_per_row;
             uint32_t src_row = row;
-            if (a.gather_idx) {
+            if (GATHER) {
                 src_row = (uint32_t)a.gather_idx[row];
                 valid = src_row < a.M_src; // also rejects negative indices
                 src_row = valid ? src_row : 0u;
@@ -130,7 +139,10 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
             dst_sf[u] = a.sf + (size_t)row * a.ld_sf + (size_t)(cc >> 3) * 4;
         }
 #if MXFP4_QUANT_NT_LOAD
-        w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        if (!GATHER || MXFP4_GATHER_NT_LOAD)
+            w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        else
+            w[u] = *reinterpret_cast<const u32x4 *>(src); // gathered rows are read several times
 #else
         w[u] = *reinterpret_cast<const u32x4 *>(src);
 #endif
@@ -147,11 +159,12 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
             break;
         uint32_t out[2], b;
         quant16(w[u], s[u], out, &b);
-#if MXFP4_QUANT_NT_STORE
-        __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
-#else
-        *reinterpret_cast<u32x2 *>(dst_q[u]) = u32x2{out[0], out[1]};
-#endif
+        // the dense output is read by the next kernel of a step; a gathered payload (several times the
+        // source) is not, and streaming it leaves the caches to the rows that are read again
+        if (MXFP4_QUANT_NT_STORE || (GATHER && MXFP4_GATHER_NT_STORE))
+            __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
+        else
+            *reinterpret_cast<u32x2 *>(dst_q[u]) = u32x2{out[0], out[1]};
 
         // lanes 2j, 2j+1 of the tile's 8 hold block j's byte: gather the four into lane 0
         uint32_t t = b | (dpp_read<DPP_QUAD_XOR2>(b) << 8); // lanes 0,1: B0 | B1 << 8
@@ -273,9 +286,11 @@ hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t
     const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
     const bool dense = gather_idx == nullptr && ld_q == K / 2 && ld_sf == K / 32;
     if (dense)
-        hipLaunchKernelGGL(quant_from_fp8_kernel<true>, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+        hipLaunchKernelGGL((quant_from_fp8_kernel<true, false>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+    else if (gather_idx)
+        hipLaunchKernelGGL((quant_from_fp8_kernel<false, true>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
     else
-        hipLaunchKernelGGL(quant_from_fp8_kernel<false>, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+        hipLaunchKernelGGL((quant_from_fp8_kernel<false, false>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
     return hipGetLastError();
 }
 
