@@ -60,11 +60,15 @@ struct RowToColArgs {
     uint32_t K;
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
+    uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
 };
 
 constexpr uint32_t MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK; // macro block of the tile order
 
 // The nibbles are read once: non-temporal loads (plain loads: 109 us against 94 at [65536,7168]).
+#ifndef MXFP4_RTC_STAGE_IN
+#define MXFP4_RTC_STAGE_IN 1
+#endif
 #ifndef MXFP4_RTC_NT_LOAD
 #define MXFP4_RTC_NT_LOAD 1
 #endif
@@ -298,7 +302,24 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             }
         }
     };
-    load_slice();
+    // With many tiles per CU a full tile arrives through 16-byte loads (8 rows x 128 bytes per wave
+    // instruction instead of 2) and is cut into the lanes' 32 x 8 slices through the tile buffer: a wave
+    // fetches the 64 rows of its own two row groups, row-major.  At [65536,7168] 87.5 us against 89.7 launched
+    // back to back and 1.3 us less inside a three-kernel step; with few tiles per CU the extra barrier and
+    // LDS round trip cost 6 %, so the launcher asks for it only on large flat grids.
+    const bool staged = a.stage_in != 0u && n_rows == (uint32_t)TILE_M && cols == (uint32_t)TILE_K &&
+                        (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
+    u32x4 stage_v[8];
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+        const uint8_t *src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u +
+                             (size_t)(wv * 64u + (lane >> 3)) * pitch + (lane & 7u) * 16u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            stage_v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (size_t)(j * 8) * pitch));
+    } else {
+        load_slice();
+    }
     load_sf();
     // ---- stage the row scales.  A wave stages two row groups; one ballot per k-block tells which
     // (row group, k-block) pairs hold a byte of 253 or more (beyond FP32, or NaN).
@@ -323,7 +344,20 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             s_special[(tid >> 6) * 2 + 1] = (uint8_t)special_hi;
         }
     }
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            s_out[(wv * 64u + j * 8u) * 8u + lane] = stage_v[j];
+    }
     __syncthreads();
+    if (staged) {
+        const uint32_t *s_in = reinterpret_cast<const uint32_t *>(s_out) + rg * 32u * 32u + cg;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            w[i] = s_in[i * 32];
+        __syncthreads(); // every slice is in registers before the tile buffer takes the results
+    }
 
     if (active) {
         const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * SF_STRIDE + rg * 32u];
@@ -429,6 +463,8 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
+    // one group of rows and at least 8 tiles per CU of an MI355X (per-expert splits: 1-2 % slower with it)
+    a.stage_in = !expert_offsets && total >= 8u * 256u && MXFP4_RTC_STAGE_IN ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
