@@ -331,13 +331,19 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
                 s_row_sf[(4 + j) * SF_STRIDE + tid] = (uint8_t)(hi >> (8 * j));
             }
         }
+        // a byte is 253 or more when its top bit is set and its low seven bits plus 3 reach 128: one test
+        // for the 8 bytes of a row and one ballot for the wave; the per-k-block ballots only run when it fires
         uint32_t special_lo = 0, special_hi = 0;
+        const uint32_t big = ((((lo & 0x7F7F7F7Fu) + 0x03030303u) & lo) | (((hi & 0x7F7F7F7Fu) + 0x03030303u) & hi)) &
+                             0x80808080u;
+        if (__ballot(big != 0u) != 0ull) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
-            const uint64_t m = __ballot(b >= 253u);
-            special_lo |= ((uint32_t)m != 0u ? 1u : 0u) << j;
-            special_hi |= ((uint32_t)(m >> 32) != 0u ? 1u : 0u) << j;
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t b = ((j < 4 ? lo : hi) >> (8 * (j & 3))) & 0xFFu;
+                const uint64_t m = __ballot(b >= 253u);
+                special_lo |= ((uint32_t)m != 0u ? 1u : 0u) << j;
+                special_hi |= ((uint32_t)(m >> 32) != 0u ? 1u : 0u) << j;
+            }
         }
         if ((tid & 63u) == 0u) {
             s_special[(tid >> 6) * 2] = (uint8_t)special_lo;
