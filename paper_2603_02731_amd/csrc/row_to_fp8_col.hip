@@ -45,6 +45,9 @@ namespace mxfp4 {
 #ifndef MXFP4_F8C_WAVES
 #define MXFP4_F8C_WAVES 1
 #endif
+#ifndef MXFP4_F8C_STAGE_IN
+#define MXFP4_F8C_STAGE_IN 1
+#endif
 #ifndef MXFP4_F8C_NT
 #define MXFP4_F8C_NT 1
 #endif
@@ -75,6 +78,7 @@ struct Args {
     uint32_t K;
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
+    uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
 };
 
 // Decode-scale operand of row I of a slice: exponent field max(127 - (bmax - b_I), 0) in bits
@@ -138,7 +142,20 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     // ---- the RPL x 8 slice of a lane: one dword (8 nibbles) per row, from a uniform row pointer
     // plus a 32-bit lane offset (one address register, not RPL pairs)
     uint32_t w[RPL];
-    if (active) {
+    // On flat grids with many tiles per CU a full tile arrives through 16-byte loads (8 rows x 128 bytes per
+    // wave instruction instead of 2) and is cut into the lanes' slices through the tile buffer, behind one
+    // more barrier: 133.6 -> 127.0 us at [65536,7168] launched back to back.
+    const bool staged = RPL == 32 && PHASES == 1 && a.stage_in != 0u && n_rows == (uint32_t)TILE_M &&
+                        cols == (uint32_t)TILE_K && (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
+    u32x4 stage_v[8];
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+        const uint8_t *src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u +
+                             (size_t)(wv * 64u + (lane >> 3)) * pitch + (lane & 7u) * 16u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            stage_v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (size_t)(j * 8) * pitch));
+    } else if (active) {
         const uint8_t *tile_src = a.q_row + (size_t)(row_base + m0) * pitch + k0 / 2u;
         const uint32_t lane_off = rgl * RPL * pitch + cg * 4u; // < 2^32: K is at most 2^24
         if (n_rows == (uint32_t)TILE_M) {
@@ -201,7 +218,20 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
                 s_nan[(row >> 6) * 8 + part * KBT + j] = (uint8_t)((nan_bits >> j) & 1u);
         }
     }
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            s_out[(wv * 64u + j * 8u) * 8u + lane] = stage_v[j];
+    }
     __syncthreads();
+    if (staged) {
+        const uint32_t *s_in = reinterpret_cast<const uint32_t *>(s_out) + rgl * 32u * 32u + cg;
+#pragma unroll
+        for (int i = 0; i < RPL; ++i)
+            w[i] = s_in[i * 32];
+        __syncthreads(); // every slice is in registers before the tile buffer takes the results
+    }
 
     // ---- the lane's view: its k-block kb, its 128-row group g
     const uint32_t kb = cg >> 2, g = (rgl * RPL) >> 7;
@@ -325,6 +355,7 @@ hipError_t launch_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, co
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
+    a.stage_in = !expert_offsets && total >= 8u * 256u && MXFP4_F8C_STAGE_IN ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();

@@ -24,6 +24,10 @@
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
+#ifndef MXFP4_F8CR_STAGE_IN
+#define MXFP4_F8CR_STAGE_IN 1
+#endif
+
 namespace mxfp4 {
 
 namespace fp8col_requant {
@@ -43,6 +47,7 @@ struct Args {
     uint32_t K;
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
+    uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
 };
 
 // Emax = biased exponent of a non-zero column maximum, plus one (FP32 subnormals: 2^-127 and
@@ -156,7 +161,19 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
 
     // ---- the 32x8 slice of a lane: one dword (8 nibbles) per row
     uint32_t w[32];
-    if (active) {
+    // On flat grids with many tiles per CU a full tile arrives through 16-byte loads (8 rows x 128 bytes per
+    // wave instruction instead of 2) and is cut into the lanes' slices through the tile buffer, behind one
+    // more barrier.
+    const bool staged = a.stage_in != 0u && n_rows == (uint32_t)TILE_M && cols == (uint32_t)TILE_K &&
+                        (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
+    u32x4 stage_v[8];
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+        const uint8_t *src = tile_src + (size_t)(wv * 64u + (lane >> 3)) * pitch + (lane & 7u) * 16u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            stage_v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (size_t)(j * 8) * pitch));
+    } else if (active) {
         const uint32_t lane_off = rg * 32u * pitch + cg * 4u; // < 2^32: K is at most 2^24
         if (n_rows == (uint32_t)TILE_M) {
 #pragma unroll
@@ -202,7 +219,20 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
                 s_special[(tid >> 6) * 8 + j] = (uint8_t)((special >> j) & 1u);
         }
     }
+    if (staged) {
+        const uint32_t wv = tid >> 6, lane = tid & 63u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            s_out[(wv * 64u + j * 8u) * 8u + lane] = stage_v[j];
+    }
     __syncthreads();
+    if (staged) {
+        const uint32_t *s_in = reinterpret_cast<const uint32_t *>(s_out) + rg * 32u * 32u + cg;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            w[i] = s_in[i * 32];
+        __syncthreads(); // every slice is in registers before the tile buffer takes the results
+    }
 
     // ---- the lane's view: its k-block kb, its 128-row group g
     const uint32_t kb = cg >> 2, g = rg >> 2;
@@ -371,6 +401,7 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
+    a.stage_in = !expert_offsets && total >= 8u * 256u && MXFP4_F8CR_STAGE_IN ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_requant_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
