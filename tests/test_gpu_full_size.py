@@ -164,3 +164,53 @@ def test_config5_dispatch_payload_round_trip(target):
     # sizes: the closed-form payloads
     assert buf.numel() == synth.payload_bytes(Mo, K)["mxfp4"]
     assert x.numel() + 4 * xsc.numel() == synth.payload_bytes(Mo, K)["fp8"]
+
+
+def test_ragged_32_experts_without_padding_65536x7168(target):
+    """The un-padded 32-expert split bench.py times (Zipf counts, any T_e): the three transposing
+    entry points against the oracle, expert by expert, with guard bytes around every output."""
+    from concurrent.futures import ThreadPoolExecutor
+    K = 7168
+    off, _ = synth.expert_offsets(seed=0, num_experts=32, total_tokens=65536 - 32 * 128, pad_to=1)
+    Mr = int(off[-1])
+    T = np.diff(off.numpy().astype(np.int64))
+    assert (T % 32 != 0).any() and (T % 2 != 0).any()
+    q, sf = target["q"][:Mr], target["sf"][:Mr]
+    qh, sfh = host(q), host(sf)
+    offd = off.to(DEV)
+    guard = 4096
+
+    def guarded(n, dtype, fill):
+        buf = torch.full((guard + n + guard,), fill, dtype=dtype, device=DEV)
+        return buf, buf[guard:guard + n]
+
+    def unguard(buf, n, fill, what):
+        b = host(buf)
+        assert (b[:guard] == fill).all() and (b[guard + n:] == fill).all(), f"{what}: written outside the output"
+        return b[guard:guard + n]
+
+    def per_expert(fn):
+        """fn on each expert's slice as a one-expert split, experts over the host threads."""
+        def one(e):
+            lo, hi = int(off[e]), int(off[e + 1])
+            return fn(qh[lo:hi], sfh[lo:hi], np.array([0, hi - lo], np.int32))
+        with ThreadPoolExecutor(16) as pool:
+            parts = list(pool.map(one, range(32)))
+        return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+
+    wqc, wsc = per_expert(ref.row_to_col_grouped)
+    qbuf, qv = guarded(wqc.size, torch.uint8, 0xA5)
+    sbuf, sv = guarded(wsc.size, torch.uint8, 0x5A)
+    mx.mxfp4_row_to_col_grouped(q, sf, offd, q_col=qv, sf_col=sv)
+    assert_same(unguard(sbuf, wsc.size, 0x5A, "sf_col"), wsc, "ragged row->col scale bytes")
+    assert_same(unguard(qbuf, wqc.size, 0xA5, "q_col"), wqc, "ragged row->col nibbles")
+    del qbuf, sbuf, wqc, wsc
+
+    for requant in (False, True):
+        wx, wxs = per_expert(lambda a, b, o: ref.row_to_fp8_col_grouped(a, b, o, requant=requant))
+        xbuf, xv = guarded(wx.size, torch.uint8, 0xA5)
+        fbuf, fv = guarded(wxs.size, torch.float32, -7.0)
+        mx.mxfp4_row_to_fp8_col_grouped(q, sf, offd, x_col=xv, x_col_scale=fv, requant=requant)
+        assert_same(unguard(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"ragged FP8 column scales, requant={requant}")
+        assert_same(unguard(xbuf, wx.size, 0xA5, "x_col"), wx, f"ragged FP8 column bytes, requant={requant}")
+        del xbuf, fbuf, wx, wxs
