@@ -24,12 +24,15 @@ __device__ __forceinline__ void write_part_out(const u32x4 *s_out, uint8_t *krow
     const uint32_t pslot = tid & 15u;
     const uint32_t lslot = (pslot - (tid >> 4)) & 15u; // 16 bytes = rows 16*lslot.. of the tile
     const uint32_t lane_off = (tid >> 4) * 8u * (uint32_t)pitch_x + lslot * 16u;
-    // Rows on 32-byte boundaries (always, unless the splits are ragged) leave with non-temporal
+    // Rows on 64-byte boundaries (always, unless the splits are ragged) leave with non-temporal
     // stores.  The others leave with plain, possibly unaligned vector stores and the L2 merges
     // the pieces of neighbouring tiles: measured with 32 un-padded experts at [61440,7168]
     // 204 us, against 258 us with non-temporal stores and 286 us with the rows realigned in
     // registers (funnel shift of neighbouring 16-byte pieces, every store naturally aligned).
-    const bool streaming = NT && ((reinterpret_cast<uintptr_t>(out_x) | pitch_x) & 31u) == 0u;
+    // A tile's 256-byte piece of a k-row must consist of whole 64-byte segments for the
+    // streaming form to pay: 32 experts of 1824 rows (32-byte boundaries) take 184 us with it
+    // and about 162 us without, 1856 rows (64-byte boundaries) 142 us with it.
+    const bool streaming = NT && ((reinterpret_cast<uintptr_t>(out_x) | pitch_x) & 63u) == 0u;
     // bytes of this lane's 16-byte piece that exist: 16, or fewer at the ragged end of a split
     const uint32_t have = lslot * 16u < n_rows ? min(16u, n_rows - lslot * 16u) : 0u;
     static_for<HALVES>([&](auto oddp) {

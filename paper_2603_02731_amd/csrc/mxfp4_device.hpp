@@ -134,64 +134,96 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
     return true;
 }
 
-// Ragged inputs: which expert owns row tile `tile` of the concatenation of all experts' tiles
-// (expert e contributes ceil(T_e / TILE_ROWS) tiles, T_e = off[e+1] - off[e]).  Uniform per
-// workgroup; every wave evaluates it on its own, 64 experts at a time: one coalesced load of the
-// offsets, a wave prefix sum of the tile counts and a ballot, instead of a serial scan whose
-// every step waits for memory.  On success `tile` becomes the tile index inside the expert, and
-// for a non-zero UNIT_A / UNIT_B, `a_before` / `b_before` the sum of ceil(T_j / UNIT) over the
-// experts before it (where its outputs start when the splits are not padded).
-template <uint32_t TILE_ROWS, uint32_t UNIT_A = 0, uint32_t UNIT_B = 0>
-__device__ __forceinline__ bool tile_of_expert(const int32_t *off, int32_t num_experts, uint32_t *tile,
-                                               uint32_t *row_base, uint32_t *rows, uint32_t *a_before = nullptr,
-                                               uint32_t *b_before = nullptr)
+// Inclusive prefix sum over the 64 lanes of a wave, in the lanes' own registers (DPP): a scan
+// inside each row of 16 lanes, then the last lane of row 0 (2) is added to row 1 (3), and lane 31
+// to the upper half.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false); // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false); // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// Ragged inputs: workgroup -> (expert, row tile inside it, k tile).  Expert e contributes
+// ceil(T_e / TILE_ROWS) row tiles, T_e = off[e+1] - off[e]; the tiles of all experts, concatenated,
+// are walked in the order of tile_of_workgroup, with the number of row tiles that really exist (the
+// launch can only bound it: with the bound in its place the ids that round the grid up would all
+// fall into the last XCD's share and the others would carry its tiles: +12 % at 32 experts).
+// Uniform per workgroup; every wave evaluates it on its own, 64 experts per lane-parallel step:
+// the offsets of all experts (at most 16 x 64) are requested at once, so the lookup waits for
+// memory once, then wave prefix sums of the tile counts and a ballot find the expert.
+// On success `tile_m` is the tile index inside the expert and, for a non-zero UNIT_A / UNIT_B,
+// `a_before` / `b_before` the sum of ceil(T_j / UNIT) over the experts before it (where its
+// outputs start when the splits are not padded).
+constexpr int MAX_EXPERT_CHUNKS = 16; // 64 experts each: MXFP4_MAX_EXPERTS of the C ABI
+template <uint32_t TILE_ROWS, uint32_t UNIT_A, uint32_t UNIT_B, uint32_t MBM, uint32_t MBK, bool K_FASTEST = false>
+__device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, int32_t num_experts, uint32_t id,
+                                                          uint32_t tiles_k, uint32_t *tile_m, uint32_t *tile_k,
+                                                          uint32_t *row_base, uint32_t *rows,
+                                                          uint32_t *a_before = nullptr, uint32_t *b_before = nullptr)
 {
     const uint32_t lane = threadIdx.x & 63u;
-    uint32_t before = 0, abefore = 0, bbefore = 0; // tiles / units of the experts in earlier chunks
-    for (int32_t base = 0; base < num_experts; base += 64) {
-        const int32_t e = base + (int32_t)lane;
-        uint32_t lo = 0, hi = 0;
-        if (e < num_experts) {
-            lo = (uint32_t)off[e];
-            hi = (uint32_t)off[e + 1];
-        }
-        const uint32_t nt = (hi - lo + TILE_ROWS - 1u) / TILE_ROWS;
-        const uint32_t na = UNIT_A ? (hi - lo + UNIT_A - 1u) / (UNIT_A ? UNIT_A : 1u) : 0u;
-        const uint32_t nb = UNIT_B ? (hi - lo + UNIT_B - 1u) / (UNIT_B ? UNIT_B : 1u) : 0u;
-        uint32_t incl = nt, aincl = na, bincl = nb; // inclusive prefix sums over the wave
+    uint32_t lo[MAX_EXPERT_CHUNKS], hi[MAX_EXPERT_CHUNKS];
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
-            incl += lane >= (uint32_t)d ? up : 0u;
-            if (UNIT_A) {
-                const uint32_t aup = (uint32_t)__shfl_up((int)aincl, d, 64);
-                aincl += lane >= (uint32_t)d ? aup : 0u;
-            }
-            if (UNIT_B) {
-                const uint32_t bup = (uint32_t)__shfl_up((int)bincl, d, 64);
-                bincl += lane >= (uint32_t)d ? bup : 0u;
-            }
+    for (int c = 0; c < MAX_EXPERT_CHUNKS; ++c) {
+        lo[c] = hi[c] = 0u;
+        if (c * 64 >= num_experts)
+            break;
+        const int32_t e = c * 64 + (int32_t)lane;
+        if (e < num_experts) {
+            lo[c] = (uint32_t)off[e];
+            hi[c] = (uint32_t)off[e + 1];
         }
-        const uint64_t hit = __ballot(before + incl > *tile);
+    }
+    uint32_t total = 0; // row tiles of all experts
+    uint32_t incl[MAX_EXPERT_CHUNKS]; // prefix sums of the tile counts inside each chunk
+#pragma unroll
+    for (int c = 0; c < MAX_EXPERT_CHUNKS; ++c) {
+        incl[c] = 0u;
+        if (c * 64 >= num_experts)
+            break;
+        incl[c] = wave_inclusive_sum((hi[c] - lo[c] + TILE_ROWS - 1u) / TILE_ROWS);
+        total += (uint32_t)__builtin_amdgcn_readlane((int)incl[c], 63);
+    }
+    uint32_t tile;
+    if (!tile_of_workgroup<MBM, MBK, K_FASTEST>(id, total, tiles_k, &tile, tile_k))
+        return false;
+
+    uint32_t before = 0, abefore = 0, bbefore = 0; // tiles / units of the experts in earlier chunks
+#pragma unroll
+    for (int c = 0; c < MAX_EXPERT_CHUNKS; ++c) {
+        if (c * 64 >= num_experts)
+            break;
+        const uint32_t len = hi[c] - lo[c];
+        const uint32_t nt = (len + TILE_ROWS - 1u) / TILE_ROWS;
+        const uint32_t na = UNIT_A ? (len + UNIT_A - 1u) / (UNIT_A ? UNIT_A : 1u) : 0u;
+        const uint32_t nb = UNIT_B ? (len + UNIT_B - 1u) / (UNIT_B ? UNIT_B : 1u) : 0u;
+        const uint32_t aincl = UNIT_A ? wave_inclusive_sum(na) : 0u;
+        const uint32_t bincl = UNIT_B ? wave_inclusive_sum(nb) : 0u;
+        const uint64_t hit = __ballot(before + incl[c] > tile);
         if (hit != 0ull) {
             const int l = __ffsll((unsigned long long)hit) - 1;
-            const uint32_t excl = (uint32_t)__builtin_amdgcn_readlane((int)(incl - nt), l);
-            *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo, l);
-            *rows = (uint32_t)__builtin_amdgcn_readlane((int)(hi - lo), l);
-            *tile -= before + excl;
+            const uint32_t excl = (uint32_t)__builtin_amdgcn_readlane((int)(incl[c] - nt), l);
+            *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo[c], l);
+            *rows = (uint32_t)__builtin_amdgcn_readlane((int)len, l);
+            *tile_m = tile - (before + excl);
             if (UNIT_A)
                 *a_before = abefore + (uint32_t)__builtin_amdgcn_readlane((int)(aincl - na), l);
             if (UNIT_B)
                 *b_before = bbefore + (uint32_t)__builtin_amdgcn_readlane((int)(bincl - nb), l);
             return true;
         }
-        before += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        before += (uint32_t)__builtin_amdgcn_readlane((int)incl[c], 63);
         if (UNIT_A)
             abefore += (uint32_t)__builtin_amdgcn_readlane((int)aincl, 63);
         if (UNIT_B)
             bbefore += (uint32_t)__builtin_amdgcn_readlane((int)bincl, 63);
     }
-    return false;
+    return false; // not reached: tile < total
 }
 
 // The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.

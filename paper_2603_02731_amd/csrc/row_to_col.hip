@@ -232,15 +232,18 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     __shared__ alignas(16) uint8_t s_col_sf[TILE_K * NRG]; // [slot c*32 + cg of column cg*8 + c][row group]
     __shared__ uint8_t s_special[NRG];                   // per row group: bit kb set = a scale byte >= 253
 
+    // ---- which tile, and which rows: the whole matrix, or one expert's slice of any length (uniform
+    // per workgroup)
     uint32_t strip, tile_k;
-    if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k))
-        return;
-
-    // ---- which rows: the whole matrix, or one expert's slice of any length (uniform per workgroup)
     uint32_t row_base = 0, rows = a.M, bytes_before = 0, blocks_before = 0;
-    if (a.expert_offsets && !tile_of_expert<TILE_M, 2, 32>(a.expert_offsets, a.num_experts, &strip, &row_base, &rows,
-                                                           &bytes_before, &blocks_before))
+    if (a.expert_offsets) {
+        if (!tile_of_grouped_workgroup<TILE_M, 2, 32, MBM, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+                                                                &strip, &tile_k, &row_base, &rows, &bytes_before,
+                                                                &blocks_before))
+            return;
+    } else if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k)) {
         return;
+    }
     const uint32_t m0 = strip * TILE_M;
     if (m0 >= rows)
         return;

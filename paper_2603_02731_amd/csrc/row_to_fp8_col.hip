@@ -110,15 +110,19 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     __shared__ alignas(8) uint8_t s_max16[8 * 16];       // [k-block][16-row group]: max of the non-NaN bytes
     __shared__ uint8_t s_nan[4 * 8];                     // [64-row group][k-block]: a NaN scale byte occurs
 
+    // ---- which tile, and which rows: the whole matrix, or one expert's slice of any length (uniform
+    // per workgroup)
     uint32_t tile_m, tile_k;
-    if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k))
-        return;
-
-    // ---- which rows: the whole matrix, or one expert's slice of any length (uniform per workgroup)
     uint32_t row_base = 0, rows = a.M, groups_before = 0;
-    if (a.expert_offsets &&
-        !tile_of_expert<TILE_M, 128>(a.expert_offsets, a.num_experts, &tile_m, &row_base, &rows, &groups_before))
+    if (a.expert_offsets) {
+        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(
+                a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k, &tile_m, &tile_k, &row_base, &rows,
+                &groups_before))
+            return;
+    } else if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(blockIdx.x, a.tiles_m, a.tiles_k,
+                                                                                     &tile_m, &tile_k)) {
         return;
+    }
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
     if (m0 >= rows)
         return;

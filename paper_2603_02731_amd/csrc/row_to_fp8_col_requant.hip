@@ -128,15 +128,17 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
     __shared__ alignas(16) float s_amax[8 * TILE_K];     // [32-row group][column]: maxima of pass 1
     __shared__ uint8_t s_special[4 * 8];                 // [64-row group][k-block]: a scale byte >= 253
 
+    // ---- which tile, and which rows: the whole matrix, or one expert's slice of any length (uniform
+    // per workgroup)
     uint32_t tile_m, tile_k;
-    if (!tile_of_workgroup<32, 4>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k))
-        return;
-
-    // ---- which rows: the whole matrix, or one expert's slice of any length (uniform per workgroup)
     uint32_t row_base = 0, rows = a.M, groups_before = 0;
-    if (a.expert_offsets &&
-        !tile_of_expert<TILE_M, 128>(a.expert_offsets, a.num_experts, &tile_m, &row_base, &rows, &groups_before))
+    if (a.expert_offsets) {
+        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, 32, 4>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+                                                              &tile_m, &tile_k, &row_base, &rows, &groups_before))
+            return;
+    } else if (!tile_of_workgroup<32, 4>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k)) {
         return;
+    }
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
     if (m0 >= rows)
         return;

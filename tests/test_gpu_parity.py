@@ -392,6 +392,34 @@ def test_grouped_more_experts_than_a_wave():
     assert_same(host(x), wx, "150 experts row->FP8 col bytes")
 
 
+def test_grouped_with_the_largest_number_of_experts():
+    # 1024 experts, the most the C ABI takes (16 lane-parallel steps of the lookup): ragged sizes 0..300,
+    # many empty, the first and last experts of every step of 64 non-empty
+    E = 1024
+    rng = np.random.default_rng(14)
+    counts = rng.integers(0, 301, size=E)
+    counts[rng.random(E) < 0.5] = 0
+    counts[::64] = 33
+    counts[63::64] = 257
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    M, K = int(off[-1]), 128
+    q, sf = synth.random_mxfp4(M, K, seed=15, scale_center=124, scale_spread=5)
+    q, sf = q.numpy(), sf.numpy()
+    offd = torch.from_numpy(off).to(DEV)
+    qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd)
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off)
+    assert_same(host(sc).reshape(-1)[:wsc.size], wsc, "1024 experts row->col scales")
+    assert_same(host(qc).reshape(-1)[:wqc.size], wqc, "1024 experts row->col nibbles")
+    for requant in (False, True):
+        x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, requant=requant)
+        wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off, requant=requant)
+        assert_same(host(xs).reshape(-1)[:wxs.size], wxs, f"1024 experts row->FP8 col scales, requant={requant}")
+        assert_same(host(x).reshape(-1)[:wx.size], wx, f"1024 experts row->FP8 col bytes, requant={requant}")
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), torch.zeros(1026, dtype=torch.int32, device=DEV))
+    assert e.value.status == -4
+
+
 @pytest.mark.parametrize("K", [256, 384])
 def test_row_to_fp8_col_ragged_splits_without_padding(K):
     # any T_e: partial last scale groups, partial tiles, unaligned rows; outputs are checked together
