@@ -118,6 +118,10 @@ def test_scale_byte_is_smallest_power_of_two_covering_gmax_over_6():
     assert ref.scale_byte(float(np.nextafter(np.float32(3), np.float32(4)))) == 127
     assert ref.scale_byte(float(np.nextafter(np.float32(6), np.float32(0)))) == 127
     assert ref.scale_byte(448.0) == 134 and ref.scale_byte(1.0) == 125 and ref.scale_byte(0.75) == 124
+    # the clamps of the byte: 2^127 is the largest scale (byte 254; 255 means NaN), byte 0 the smallest.  No
+    # finite FP32 maximum needs the upper one (6 * 2^127 exceeds FP32), so it is pinned on doubles.
+    assert ref.scale_byte(6 * 2.0 ** 127) == 254 and ref.scale_byte(6 * 2.0 ** 128) == 254 and ref.scale_byte(2.0 ** 300) == 254
+    assert ref.scale_byte(6 * 2.0 ** -127) == 0 and ref.scale_byte(2.0 ** -149) == 0 and ref.scale_byte(6 * 2.0 ** -126) == 1
     gs = [float(np.float32(2.0 ** rng.uniform(-149, 127.9))) for _ in range(4000)]
     gs += [float(np.float32(6 * 2.0 ** k)) for k in range(-130, 125)]
     gs += [float(np.nextafter(np.float32(6 * 2.0 ** k), np.float32(np.inf))) for k in range(-125, 125)]
