@@ -214,3 +214,26 @@ def test_ragged_32_experts_without_padding_65536x7168(target):
         assert_same(unguard(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"ragged FP8 column scales, requant={requant}")
         assert_same(unguard(xbuf, wx.size, 0xA5, "x_col"), wx, f"ragged FP8 column bytes, requant={requant}")
         del xbuf, fbuf, wx, wxs
+
+
+def test_large_grids_with_inputs_on_4_byte_boundaries():
+    """[16384, 8192] is 2048 tiles, where full tiles fetch their nibbles with 16-byte loads; an input that only
+    has the 4-byte alignment the entry points ask for must take the dword loads instead, with the same result."""
+    M, K = 16384, 8192
+    q, sf = synth.random_mxfp4(M, K, seed=21, scale_center=120, scale_spread=7, nan_scale_frac=0.0005)
+    qh, sfh = q.numpy(), sf.numpy()
+    buf = torch.empty(M * K // 2 + 16, dtype=torch.uint8, device=DEV)
+    for shift in (0, 4):
+        qd = buf[shift:shift + M * K // 2].view(M, K // 2)
+        qd.copy_(q.to(DEV))
+        assert qd.data_ptr() % 16 == shift
+        sfd = sf.to(DEV)
+        qc, sc = mx.mxfp4_row_to_col(qd, sfd)
+        wqc, wsc = par.row_to_col(qh, sfh)
+        assert_same(host(sc), wsc, f"column scale bytes, input at +{shift}")
+        assert_same(host(qc), wqc, f"column nibbles, input at +{shift}")
+        for requant in (False, True):
+            x, xs = mx.mxfp4_row_to_fp8_col(qd, sfd, requant=requant)
+            wx, wxs = par.row_to_fp8_col(qh, sfh, requant=requant)
+            assert_same(host(xs), wxs, f"FP8 column scales, input at +{shift}, requant={requant}")
+            assert_same(host(x), wx, f"FP8 column bytes, input at +{shift}, requant={requant}")
