@@ -1,6 +1,7 @@
 // The C ABI of libmxfp4 (include/mxfp4.h): argument validation and kernel launches.
 // Nothing here allocates, copies or synchronises.
 #include "../../include/mxfp4.h"
+#include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
 namespace {
@@ -11,6 +12,7 @@ inline mxfp4_status launched(hipError_t e) { return e == hipSuccess ? MXFP4_OK :
 
 constexpr int64_t kMaxWorkItems = ((int64_t)1 << 32) - 4096; // kernels index their work with 32 bits
 constexpr int64_t kMaxRows = (int64_t)1 << 31;
+static_assert(mxfp4::MAX_EXPERT_CHUNKS * 64 >= MXFP4_MAX_EXPERTS, "the expert lookup of the grouped kernels holds every expert's offsets");
 
 } // namespace
 
