@@ -11,6 +11,9 @@ SOURCES = ["mxfp4_api.hip", "quant_from_fp8.hip", "quant_from_bf16.hip", "dequan
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-command-line-argument",
          "-ffp-contract=off",
+         # the expert lookup's last loop keeps its early exit instead of being unrolled 16 times (its arrays stay
+         # in registers all the same, and it is the faster form): no remark about it
+         "-Wno-pass-failed",
          # packed-FP32 instructions are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
