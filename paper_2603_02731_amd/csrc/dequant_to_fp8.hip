@@ -40,9 +40,16 @@
 
 namespace mxfp4 {
 
-constexpr int DEQUANT_THREADS = 256;
+// One run of 1024 chunks per workgroup: with the streaming stores a workgroup's output should be one long
+// contiguous piece (16 KiB) written by as many lanes as a workgroup can have.  Measured at [65536,7168]
+// inside the step: 256 lanes x 2 runs 107.5 us, 256 x 1 105.4, 512 x 1 104.2, 1024 x 1 102.8, 128 x 1 105.1,
+// 64 x 1 108.1; more than one run per lane with 1024 lanes, or more than two with 256: 124 us.
+#ifndef MXFP4_DEQUANT_THREADS
+#define MXFP4_DEQUANT_THREADS 1024
+#endif
+constexpr int DEQUANT_THREADS = MXFP4_DEQUANT_THREADS;
 #ifndef MXFP4_DEQUANT_UNROLL
-#define MXFP4_DEQUANT_UNROLL 2
+#define MXFP4_DEQUANT_UNROLL 1
 #endif
 constexpr int DEQUANT_UNROLL = MXFP4_DEQUANT_UNROLL;
 
@@ -106,7 +113,7 @@ struct DequantArgs {
     uint32_t halves_per_row; // K / 16
 };
 
-// One workgroup covers DEQUANT_UNROLL runs of 256 consecutive half-blocks; a lane takes
+// One workgroup covers DEQUANT_UNROLL runs of DEQUANT_THREADS consecutive half-blocks; a lane takes
 // half-block `tid` of each run: 512 B loaded and 1 KiB stored per wave instruction, both
 // contiguous, which is what lets the stores go out non-temporally at full rate.
 template <bool DENSE>
