@@ -19,7 +19,7 @@ namespace mxfp4 {
 #define MXFP4_QBF16_STREAM_STORE 0
 #endif
 
-constexpr int QBF_THREADS = 256;
+constexpr int QBF_THREADS = 512; // 512 lanes x 2 runs: 182-184 us at [65536,7168], 256 x 2 185, 1024 x 2 189, one run per lane 193-218
 constexpr int QBF_UNROLL = 2;
 
 struct QuantBf16Args {
