@@ -110,3 +110,70 @@ def test_grouped_entry_points_on_random_splits(seed):
         mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, x_col=xv, x_col_scale=fv, requant=requant)
         same(check_guards(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"grouped FP8 col scales T={T} K={K} requant={requant}")
         same(check_guards(xbuf, wx.size, 0xA5, "x_col"), wx, f"grouped FP8 col bytes T={T} K={K} requant={requant}")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_strided_and_routed_forms_on_random_shapes(seed):
+    """The non-dense kernel instances: gathered rows into padded planes and into per-token records, the
+    de-quantizer reading those, the scatter form with a random fan-out, the BF16 quantizer into padded
+    planes; bytes between the rows of a padded output must stay as they were."""
+    rng = np.random.default_rng(4000 + seed)
+    M_src = int(rng.integers(1, 700))
+    K = 128 * int(rng.integers(1, 9))
+    v = (rng.standard_t(3, size=(M_src, K)) * 10.0 ** rng.uniform(-3, 3)).astype(np.float32)
+    x8, s = synth.fp8_blockwise_quantize(torch.from_numpy(v))
+    x8, s = x8.numpy(), s.numpy()
+    xd, sd = dev(x8), dev(s)
+
+    # gather into planes whose rows are padded
+    M_out = int(rng.integers(1, 1500))
+    idx = rng.integers(0, M_src, M_out).astype(np.int32)
+    wq, wsf = ref.quant_from_fp8(x8, s, gather_idx=idx)
+    ld_q = K // 2 + 8 * int(rng.integers(0, 5))
+    ld_sf = K // 32 + 4 * int(rng.integers(0, 5))
+    qbuf = torch.full((M_out * ld_q,), 0xA5, dtype=torch.uint8, device=DEV)
+    sbuf = torch.full((M_out * ld_sf,), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8(xd, sd, gather_idx=dev(idx), q=qbuf, sf=sbuf, ld_q=ld_q, ld_sf=ld_sf)
+    qh, sh = host(qbuf).reshape(M_out, ld_q), host(sbuf).reshape(M_out, ld_sf)
+    same(qh[:, :K // 2], wq, f"gathered nibbles, ld_q={ld_q}")
+    same(sh[:, :K // 32], wsf, f"gathered scales, ld_sf={ld_sf}")
+    assert (qh[:, K // 2:] == 0xA5).all() and (sh[:, K // 32:] == 0x5A).all(), "padding between rows written"
+
+    # one record per token (nibbles, scales, padding to 16 bytes), and the de-quantizer reading the records
+    rec = (K // 2 + K // 32 + 15) // 16 * 16 + 16 * int(rng.integers(0, 3))
+    rbuf = torch.full((M_out * rec,), 0xC3, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8(xd, sd, gather_idx=dev(idx), q=rbuf, sf=rbuf[K // 2:], ld_q=rec, ld_sf=rec)
+    rh = host(rbuf).reshape(M_out, rec)
+    same(rh[:, :K // 2], wq, f"record nibbles, record of {rec} bytes")
+    same(rh[:, K // 2:K // 2 + K // 32], wsf, "record scales")
+    assert (rh[:, K // 2 + K // 32:] == 0xC3).all(), "padding of the records written"
+    x, xs = mx.mxfp4_dequant_to_fp8(rbuf, rbuf[K // 2:], M=M_out, K=K, ld_q=rec, ld_sf=rec)
+    wx, wxs = ref.dequant_to_fp8(wq, wsf)
+    same(host(xs), wxs, "tile scales from records")
+    same(host(x), wx, "E4M3 bytes from records")
+
+    # the routing turned around: random fan-out, some entries pointing nowhere
+    fanout = int(rng.integers(1, 10))
+    M_dst = M_src * fanout + int(rng.integers(0, 50))
+    slots = rng.permutation(M_dst)[:M_src * fanout].astype(np.int32).reshape(M_src, fanout)
+    nowhere = rng.random(slots.shape) < 0.1
+    slots[nowhere] = rng.choice(np.array([-1, M_dst, 2 ** 31 - 1], np.int32), size=int(nowhere.sum()))
+    wq2, wsf2 = ref.quant_from_fp8_scatter(x8, s, slots, M_dst, q=np.full((M_dst, K // 2), 0xA5, np.uint8),
+                                           sf=np.full((M_dst, K // 32), 0x5A, np.uint8))
+    q2 = torch.full((M_dst, K // 2), 0xA5, dtype=torch.uint8, device=DEV)
+    sf2 = torch.full((M_dst, K // 32), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_fp8_scatter(xd, sd, dev(slots), M_dst, q=q2, sf=sf2)
+    same(host(sf2), wsf2, f"scattered scales, fanout {fanout}")
+    same(host(q2), wq2, f"scattered nibbles, fanout {fanout}")
+
+    # BF16 source into padded planes
+    xb = torch.from_numpy(v).to(torch.bfloat16)
+    wq3, wsf3 = ref.quant_from_bf16(xb.view(torch.int16).numpy().view(np.uint16))
+    ld_q3 = K // 2 + 4 * int(rng.integers(0, 5))
+    q3 = torch.full((M_src * ld_q3,), 0xA5, dtype=torch.uint8, device=DEV)
+    s3 = torch.full((M_src * ld_sf,), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mxfp4_quant_from_bf16(xb.to(DEV), q=q3, sf=s3, ld_q=ld_q3, ld_sf=ld_sf)
+    q3h, s3h = host(q3).reshape(M_src, ld_q3), host(s3).reshape(M_src, ld_sf)
+    same(q3h[:, :K // 2], wq3, f"BF16 nibbles, ld_q={ld_q3}")
+    same(s3h[:, :K // 32], wsf3, "BF16 scales")
+    assert (q3h[:, K // 2:] == 0xA5).all() and (s3h[:, K // 32:] == 0x5A).all(), "padding between rows written"
