@@ -17,12 +17,15 @@
 
 namespace mxfp4 {
 
-// 512 lanes x 2 runs per workgroup: 111.0 us at [65536,7168] inside the step, against 112.6 with 256 x 2,
-// 116.2 with 1024 x 2, 118.9 with 512 x 1 and 128.7 with 1024 x 1.
+// Lanes per workgroup (each lane takes QUANT_UNROLL chunks).  Dense rows: 512 x 2 runs, 111.0 us at [65536,7168]
+// inside the step against 112.6 with 256 x 2, 116.2 with 1024 x 2, 118.9 with 512 x 1 and 128.7 with 1024 x 1.
+// Gathered, strided and scattered rows: 256 (top-8 gather 1015 us against 1035 with 512, records 1041 against
+// 1056, scatter 462 against 466).
 #ifndef MXFP4_QUANT_THREADS
 #define MXFP4_QUANT_THREADS 512
 #endif
-constexpr int QUANT_THREADS = MXFP4_QUANT_THREADS;
+constexpr int QUANT_THREADS = MXFP4_QUANT_THREADS; // dense rows
+constexpr int QUANT_THREADS_ROUTED = 256;          // gathered, strided, scattered rows
 #ifndef MXFP4_QUANT_UNROLL
 #define MXFP4_QUANT_UNROLL 2
 #endif
@@ -115,14 +118,14 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
 #ifndef MXFP4_QUANT_STREAM_SCALE
 #define MXFP4_QUANT_STREAM_SCALE 0
 #endif
-// One workgroup covers QUANT_UNROLL runs of QUANT_THREADS consecutive chunks; a lane takes chunk
+// One workgroup covers QUANT_UNROLL runs of THREADS consecutive chunks; a lane takes chunk
 // `tid` of each run, so every load and store instruction of a wave stays contiguous
 // (1 KiB in, 512 B out) while each lane keeps QUANT_UNROLL loads in flight.
 // DENSE: no gather and dense outputs -- every address is a multiple of the flat chunk index.
-template <bool DENSE, bool GATHER>
-__global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const QuantArgs a)
+template <bool DENSE, bool GATHER, int THREADS>
+__global__ void __launch_bounds__(THREADS) quant_from_fp8_kernel(const QuantArgs a)
 {
-    const uint32_t c0 = blockIdx.x * (QUANT_THREADS * QUANT_UNROLL) + threadIdx.x;
+    const uint32_t c0 = blockIdx.x * (THREADS * QUANT_UNROLL) + threadIdx.x;
 
     u32x4 w[QUANT_UNROLL];
     float s[QUANT_UNROLL];
@@ -130,7 +133,7 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
     uint8_t *dst_sf[QUANT_UNROLL]; // the tile's four scale bytes (one aligned dword)
 #pragma unroll
     for (int u = 0; u < QUANT_UNROLL; ++u) {
-        const uint32_t c = c0 + u * QUANT_THREADS;
+        const uint32_t c = c0 + u * THREADS;
         if (c >= a.n_chunks)
             break; // n_chunks is a multiple of 8: the 8 lanes of a tile leave together
         const uint8_t *src;
@@ -172,7 +175,7 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_kernel(const Qua
 
 #pragma unroll
     for (int u = 0; u < QUANT_UNROLL; ++u) {
-        if (c0 + u * QUANT_THREADS >= a.n_chunks)
+        if (c0 + u * THREADS >= a.n_chunks)
             break;
         uint32_t out[2], b;
         quant16(w[u], s[u], out, &b);
@@ -217,15 +220,15 @@ struct QuantScatterArgs {
     uint32_t M_out;
 };
 
-__global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_scatter_kernel(const QuantScatterArgs a)
+__global__ void __launch_bounds__(QUANT_THREADS_ROUTED) quant_from_fp8_scatter_kernel(const QuantScatterArgs a)
 {
-    const uint32_t c0 = blockIdx.x * (QUANT_THREADS * QUANT_UNROLL) + threadIdx.x;
+    const uint32_t c0 = blockIdx.x * (QUANT_THREADS_ROUTED * QUANT_UNROLL) + threadIdx.x;
 
     u32x4 w[QUANT_UNROLL];
     float s[QUANT_UNROLL];
 #pragma unroll
     for (int u = 0; u < QUANT_UNROLL; ++u) {
-        const uint32_t c = c0 + u * QUANT_THREADS;
+        const uint32_t c = c0 + u * QUANT_THREADS_ROUTED;
         if (c >= a.n_chunks)
             break; // n_chunks is a multiple of 8: the 8 lanes of a tile leave together
         w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.x + (size_t)c * 16));
@@ -234,7 +237,7 @@ __global__ void __launch_bounds__(QUANT_THREADS) quant_from_fp8_scatter_kernel(c
 
 #pragma unroll
     for (int u = 0; u < QUANT_UNROLL; ++u) {
-        const uint32_t c = c0 + u * QUANT_THREADS;
+        const uint32_t c = c0 + u * QUANT_THREADS_ROUTED;
         if (c >= a.n_chunks)
             break;
         uint32_t out[2], b;
@@ -288,9 +291,9 @@ hipError_t launch_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale,
     a.chunks_per_row = (uint32_t)(K / 16);
     a.fanout = (uint32_t)fanout;
     a.M_out = (uint32_t)M_out;
-    constexpr uint32_t per_block = QUANT_THREADS * QUANT_UNROLL;
+    constexpr uint32_t per_block = QUANT_THREADS_ROUTED * QUANT_UNROLL;
     const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
-    hipLaunchKernelGGL(quant_from_fp8_scatter_kernel, dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+    hipLaunchKernelGGL(quant_from_fp8_scatter_kernel, dim3(blocks), dim3(QUANT_THREADS_ROUTED), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -310,15 +313,18 @@ hipError_t launch_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t
     a.chunks_per_row = (uint32_t)(K / 16);
     a.K = (uint32_t)K;
     a.M_src = (uint32_t)M_src;
-    constexpr uint32_t per_block = QUANT_THREADS * QUANT_UNROLL;
-    const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
     const bool dense = gather_idx == nullptr && ld_q == K / 2 && ld_sf == K / 32;
+    const uint32_t per_block = (dense ? QUANT_THREADS : QUANT_THREADS_ROUTED) * QUANT_UNROLL;
+    const uint32_t blocks = (a.n_chunks + per_block - 1) / per_block;
     if (dense)
-        hipLaunchKernelGGL((quant_from_fp8_kernel<true, false>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+        hipLaunchKernelGGL((quant_from_fp8_kernel<true, false, QUANT_THREADS>), dim3(blocks), dim3(QUANT_THREADS), 0,
+                           stream, a);
     else if (gather_idx)
-        hipLaunchKernelGGL((quant_from_fp8_kernel<false, true>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+        hipLaunchKernelGGL((quant_from_fp8_kernel<false, true, QUANT_THREADS_ROUTED>), dim3(blocks),
+                           dim3(QUANT_THREADS_ROUTED), 0, stream, a);
     else
-        hipLaunchKernelGGL((quant_from_fp8_kernel<false, false>), dim3(blocks), dim3(QUANT_THREADS), 0, stream, a);
+        hipLaunchKernelGGL((quant_from_fp8_kernel<false, false, QUANT_THREADS_ROUTED>), dim3(blocks),
+                           dim3(QUANT_THREADS_ROUTED), 0, stream, a);
     return hipGetLastError();
 }
 
