@@ -27,7 +27,8 @@
 #endif
 // The E4M3 bytes, two thirds of the kernel's traffic and written in address order by the whole grid, leave
 // with streaming stores (store_streaming: 116.7 -> 108.6 us at [65536,7168] against the non-temporal hint
-// alone).  The 4-byte tile scales must not: 146 us with them streamed.
+// alone; with the nibbles coming from HBM instead of the cache: 120-123 -> 120 us).  The 4-byte tile scales must
+// not: 146 us with them streamed.
 #ifndef MXFP4_DEQUANT_STREAM_STORE
 #define MXFP4_DEQUANT_STREAM_STORE 1
 #endif
@@ -40,16 +41,17 @@
 
 namespace mxfp4 {
 
-// One run of 1024 chunks per workgroup: with the streaming stores a workgroup's output should be one long
-// contiguous piece (16 KiB) written by as many lanes as a workgroup can have.  Measured at [65536,7168]
-// inside the step: 256 lanes x 2 runs 107.5 us, 256 x 1 105.4, 512 x 1 104.2, 1024 x 1 102.8, 128 x 1 105.1,
-// 64 x 1 108.1; more than one run per lane with 1024 lanes, or more than two with 256: 124 us.
+// 128 lanes x 2 runs per workgroup.  Measured at [65536,7168] with the streaming stores, inside the step (where
+// the nibbles were written by the kernel before and still sit in the memory-side cache) / launched on its own
+// after a 470 MB copy (nibbles from HBM): 128 x 2 103.0 / 119 us, 256 x 2 107.4 / 118.5, 512 x 2 111.4 / 119.5,
+// 1024 x 1 103.1 / 135, 512 x 1 104.2 / 122, 256 x 1 105.6 / 125, 128 x 4 117.5 / 124, 64 x 4 106.6 / 124.
+// One load in flight per lane is enough when the input comes from the cache and not when it comes from memory.
 #ifndef MXFP4_DEQUANT_THREADS
-#define MXFP4_DEQUANT_THREADS 1024
+#define MXFP4_DEQUANT_THREADS 128
 #endif
 constexpr int DEQUANT_THREADS = MXFP4_DEQUANT_THREADS;
 #ifndef MXFP4_DEQUANT_UNROLL
-#define MXFP4_DEQUANT_UNROLL 1
+#define MXFP4_DEQUANT_UNROLL 2
 #endif
 constexpr int DEQUANT_UNROLL = MXFP4_DEQUANT_UNROLL;
 
