@@ -32,9 +32,6 @@
 #ifndef MXFP4_DEQUANT_STREAM_STORE
 #define MXFP4_DEQUANT_STREAM_STORE 1
 #endif
-#ifndef MXFP4_DEQUANT_STREAM_SCALE
-#define MXFP4_DEQUANT_STREAM_SCALE 0
-#endif
 #ifndef MXFP4_DEQUANT_NT_STORE
 #define MXFP4_DEQUANT_NT_STORE 1
 #endif
@@ -211,11 +208,7 @@ __global__ void __launch_bounds__(DEQUANT_THREADS) dequant_to_fp8_kernel(const D
             const int b8 = (int)bmax - 6;
             uint32_t bits = b8 >= 1 ? (uint32_t)b8 << 23 : 0x00400000u >> (uint32_t)(-b8);
             bits = any_nan ? 0x7fc00000u : bits;
-#if MXFP4_DEQUANT_STREAM_SCALE
-            store_streaming(&a.x_scale[c >> 3], bits);
-#else
             a.x_scale[c >> 3] = u2f(bits);
-#endif
         }
     }
 }

@@ -18,9 +18,6 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 // one 32-bit lane offset (M <= 2^24).  n_rows = rows of the tile that exist (1..256).
 // store_streaming instead of the non-temporal hint: 128 -> 139 us at [65536,7168].  The 256-byte pieces of
 // neighbouring tiles are better merged in the caches than written through one by one.
-#ifndef MXFP4_F8C_STREAM_STORE
-#define MXFP4_F8C_STREAM_STORE 0
-#endif
 template <int CP, int T, bool NT>
 __device__ __forceinline__ void write_part_out(const u32x4 *s_out, uint8_t *krow0, const uint8_t *out_x, size_t pitch_x,
                                                uint32_t cols, uint32_t n_rows, uint32_t tid)
@@ -47,11 +44,7 @@ __device__ __forceinline__ void write_part_out(const u32x4 *s_out, uint8_t *krow
 #pragma unroll
                 for (int c = 0; c < CP; ++c) {
                     uint8_t *dst = krow0 + (size_t)(odd * 128u + c) * pitch_x + lane_off;
-#if MXFP4_F8C_STREAM_STORE
-                    store_streaming(dst, s_out[(HALVES * c + odd) * T + tid]);
-#else
                     __builtin_nontemporal_store(s_out[(HALVES * c + odd) * T + tid], reinterpret_cast<u32x4 *>(dst));
-#endif
                 }
             } else if (have == 16u) {
                 // any alignment: global memory takes unaligned vector stores

@@ -236,14 +236,6 @@ __device__ __forceinline__ void store_streaming(void *p, u32x4 v)
 {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ void store_streaming(void *p, u32x2 v)
-{
-    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
-}
-__device__ __forceinline__ void store_streaming(void *p, uint32_t v)
-{
-    asm volatile("global_store_dword %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
-}
 
 // The first n (1..15) bytes of v to dst, any alignment, in at most four pieces.
 __device__ __forceinline__ void store_head_bytes(uint8_t *dst, const u32x4 v, uint32_t n)

@@ -15,9 +15,6 @@
 namespace mxfp4 {
 
 // store_streaming instead of the non-temporal hint: 185 -> 186 us at [65536,7168], not used.
-#ifndef MXFP4_QBF16_STREAM_STORE
-#define MXFP4_QBF16_STREAM_STORE 0
-#endif
 
 constexpr int QBF_THREADS = 512; // 512 lanes x 2 runs: 182-184 us at [65536,7168], 256 x 2 185, 1024 x 2 189, one run per lane 193-218
 constexpr int QBF_UNROLL = 2;
@@ -83,11 +80,7 @@ __global__ void __launch_bounds__(QBF_THREADS) quant_from_bf16_kernel(const Quan
             dst_q = a.q + (size_t)row * a.ld_q + (size_t)cc * 4;
             dst_sf = a.sf + (size_t)row * a.ld_sf + (size_t)(cc >> 4) * 4;
         }
-#if MXFP4_QBF16_STREAM_STORE
-        store_streaming(dst_q, r);
-#else
         __builtin_nontemporal_store(r, reinterpret_cast<uint32_t *>(dst_q));
-#endif
 
         // lanes 4j..4j+3 of a row of 16 hold block j's byte: gather the four into lane 0
         uint32_t t = b | (row_shift_left4(b) << 8); // lanes 0..3: B0 | B1 << 8; lanes 8..11: B2 | B3 << 8

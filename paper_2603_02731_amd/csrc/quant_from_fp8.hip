@@ -109,15 +109,7 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
 // store_streaming instead of the non-temporal hint, measured at [65536,7168]: the 8-byte nibble stores of the
 // dense kernel 112.0 -> 112.1 us (no difference), its scale dwords 112 -> 121 us, the scattered rows
 // 463 -> 466 us, gathered per-token records 1065 -> 1400 us: not used here.
-#ifndef MXFP4_SCATTER_STREAM_STORE
-#define MXFP4_SCATTER_STREAM_STORE 0
-#endif
-#ifndef MXFP4_QUANT_STREAM_STORE
-#define MXFP4_QUANT_STREAM_STORE 0
-#endif
-#ifndef MXFP4_QUANT_STREAM_SCALE
-#define MXFP4_QUANT_STREAM_SCALE 0
-#endif
+//
 // One workgroup covers QUANT_UNROLL runs of THREADS consecutive chunks; a lane takes chunk
 // `tid` of each run, so every load and store instruction of a wave stays contiguous
 // (1 KiB in, 512 B out) while each lane keeps QUANT_UNROLL loads in flight.
@@ -182,11 +174,7 @@ __global__ void __launch_bounds__(THREADS) quant_from_fp8_kernel(const QuantArgs
         // the dense output is read by the next kernel of a step; a gathered payload (several times the
         // source) is not, and streaming it leaves the caches to the rows that are read again
         if (MXFP4_QUANT_NT_STORE || (GATHER && MXFP4_GATHER_NT_STORE))
-#if MXFP4_QUANT_STREAM_STORE
-            store_streaming(dst_q[u], u32x2{out[0], out[1]});
-#else
             __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
-#endif
         else
             *reinterpret_cast<u32x2 *>(dst_q[u]) = u32x2{out[0], out[1]};
 
@@ -194,11 +182,7 @@ __global__ void __launch_bounds__(THREADS) quant_from_fp8_kernel(const QuantArgs
         uint32_t t = b | (dpp_read<DPP_QUAD_XOR2>(b) << 8); // lanes 0,1: B0 | B1 << 8
         t |= row_shift_left4(t) << 16;                       // lane 0: ... | B2 << 16 | B3 << 24
         if ((threadIdx.x & 7u) == 0u) {
-#if MXFP4_QUANT_STREAM_SCALE
-            store_streaming(dst_sf[u], t);
-#else
             *reinterpret_cast<uint32_t *>(dst_sf[u]) = t;
-#endif
         }
     }
 }
@@ -260,9 +244,7 @@ __global__ void __launch_bounds__(QUANT_THREADS_ROUTED) quant_from_fp8_scatter_k
             for (int j = 0; j < 8; ++j) {
                 if (d[j] >= a.M_out) // also skips negative entries and the tail of the batch
                     continue;
-#if MXFP4_SCATTER_STREAM_STORE
-                store_streaming(a.q + (size_t)d[j] * a.ld_q + (size_t)cc * 8, u32x2{out[0], out[1]});
-#elif MXFP4_SCATTER_NT_STORE
+#if MXFP4_SCATTER_NT_STORE
                 __builtin_nontemporal_store(u32x2{out[0], out[1]},
                                             reinterpret_cast<u32x2 *>(a.q + (size_t)d[j] * a.ld_q + (size_t)cc * 8));
 #else

@@ -28,9 +28,6 @@ namespace mxfp4 {
 
 // store_streaming for the 128-byte output rows: 90.5 -> 100.8 us at [65536,7168] (the non-temporal hint
 // alone: +5 %), so they are plain stores.
-#ifndef MXFP4_RTC_STREAM_STORE
-#define MXFP4_RTC_STREAM_STORE 0
-#endif
 #ifndef MXFP4_RTC_NRG
 #define MXFP4_RTC_NRG 8
 #endif
@@ -445,13 +442,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         if (cgx * 8u < cols && have != 0u) {
             if (have == 16u && aligned16) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-#if MXFP4_RTC_STREAM_STORE
-                    store_streaming(dst + (size_t)u * pitch_q, s_out[u * T_THREADS + tid]);
-#else
+                for (int u = 0; u < 8; ++u)
                     *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
-#endif
-                }
             } else if (have == 16u) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
