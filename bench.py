@@ -143,7 +143,7 @@ def main():
 
     for _ in range(a.warmup):
         step()
-    stride = max(1, a.event_stride)
+    stride = max(1, min(a.event_stride, a.steps // 8))  # at least eight bracketed steps, all of them in a short run
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] if i % stride == 0 else None
               for i in range(a.steps)]
     torch.cuda.synchronize()
