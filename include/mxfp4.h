@@ -121,8 +121,9 @@ mxfp4_status mxfp4_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, int64
  *   expert_offsets  int32 [num_experts + 1] on the DEVICE: rows [off_e, off_{e+1}) belong to
  *                   expert e; off_0 = 0, off_E = M_total, non-decreasing; every
  *                   T_e = off_{e+1} - off_e may be ANY length >= 0 (no padding needed).
+ *                   The pointer must be 4-byte aligned in every grouped form.
  * Quantization is row-independent, so the grouped form produces exactly what the flat form
- * produces on M_total rows (dense outputs).
+ * produces on M_total rows (dense outputs); it checks the pointer and the count, and reads no offset.
  * Grouped row->column writes expert e as its own dense [K, ceil(T_e/2)] and [K, ceil(T_e/32)]
  * matrices at byte offsets K * sum_{j<e} ceil(T_j/2) of q_col and K * sum_{j<e} ceil(T_j/32) of
  * sf_col (= K*off_e/2 and K*off_e/32 when every T_e is a multiple of 32): contiguous storage
@@ -185,6 +186,14 @@ mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const ui
                                                   const int32_t *expert_offsets, int32_t num_experts,
                                                   int64_t M_total, int64_t K, uint8_t *x_col,
                                                   float *x_col_scale, void *hip_stream);
+
+/* Measurement aid, not a conversion: a plain copy of `bytes` bytes with one 16-byte load and one 16-byte
+ * store per lane, the access width of the conversion kernels.  The conversions are bandwidth-bound (the
+ * paper places their cost in global-memory traffic, sec. 3.4 and 4.3), so their rates are reported beside
+ * what this copy reaches on the same GPU in the same run.
+ *   src, dst  device pointers, 16-byte aligned, not overlapping;  bytes a multiple of 16
+ *   policy    bit 0: non-temporal loads, bit 1: non-temporal stores (0..3) */
+mxfp4_status mxfp4_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, void *hip_stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp4_status_string(mxfp4_status status);

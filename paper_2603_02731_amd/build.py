@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmxfp4.so")
 SOURCES = ["mxfp4_api.hip", "quant_from_fp8.hip", "quant_from_bf16.hip", "dequant_to_fp8.hip", "row_to_col.hip",
-           "row_to_fp8_col.hip", "row_to_fp8_col_requant.hip"]
+           "row_to_fp8_col.hip", "row_to_fp8_col_requant.hip", "stream_copy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-command-line-argument",
          "-ffp-contract=off",

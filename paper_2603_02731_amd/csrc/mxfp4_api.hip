@@ -131,6 +131,8 @@ mxfp4_status mxfp4_quant_from_fp8_grouped(const uint8_t *x, const float *x_scale
         return MXFP4_ERR_OFFSETS;
     if (!expert_offsets)
         return MXFP4_ERR_NULL;
+    if (!aligned(expert_offsets, 4))
+        return MXFP4_ERR_ALIGN;
     // rows are independent: the expert boundaries do not change any output byte
     return mxfp4_quant_from_fp8(x, x_scale, M_total, K, nullptr, M_total, q, K / 2, sf, K / 32, hip_stream);
 }
@@ -207,6 +209,19 @@ mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const ui
         return MXFP4_ERR_NULL;
     return row_to_fp8_col_common(q_row, sf_row, expert_offsets, num_experts, M_total, K, x_col, x_col_scale,
                                  hip_stream, true);
+}
+
+mxfp4_status mxfp4_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, void *hip_stream)
+{
+    if (bytes < 0 || bytes % 16 != 0 || policy < 0 || policy > 3 || bytes / 16 / 1024 >= ((int64_t)1 << 31))
+        return MXFP4_ERR_SHAPE;
+    if (bytes == 0)
+        return MXFP4_OK;
+    if (!src || !dst)
+        return MXFP4_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_stream_copy(src, dst, bytes, policy, static_cast<hipStream_t>(hip_stream)));
 }
 
 const char *mxfp4_status_string(mxfp4_status status)

@@ -37,4 +37,8 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
                                          int32_t num_experts, int64_t M, int64_t K, uint8_t *x_col,
                                          float *x_col_scale, hipStream_t stream);
 
+// Plain 16-byte-per-lane copy of `bytes` (a multiple of 16) bytes; policy bit 0 = non-temporal loads,
+// bit 1 = non-temporal stores.
+hipError_t launch_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, hipStream_t stream);
+
 } // namespace mxfp4

@@ -4,6 +4,9 @@ import ctypes
 import os
 import re
 
+import pytest
+import torch
+
 import paper_2603_02731_amd as mx
 from paper_2603_02731_amd import binding
 
@@ -67,12 +70,147 @@ def test_argument_validation_without_a_gpu():
     # expert count
     assert L.mxfp4_row_to_col_grouped(a16, a16, a16, 0, 32, 128, a16, a16, None) == binding.ERR_OFFSETS
     assert L.mxfp4_quant_from_fp8_grouped(a16, a16, a16, 5000, 32, 128, a16, a16, None) == binding.ERR_OFFSETS
+    assert L.mxfp4_quant_from_fp8_grouped(a16, a16, odd, 2, 32, 128, a16, a16, None) == binding.ERR_ALIGN
+    assert L.mxfp4_row_to_col_grouped(a16, a16, odd, 2, 32, 128, a16, a16, None) == binding.ERR_ALIGN
     # empty inputs are fine and launch nothing
     assert L.mxfp4_quant_from_fp8(None, None, 0, 128, None, 0, None, 64, None, 4, None) == binding.OK
     assert L.mxfp4_dequant_to_fp8(None, 64, None, 4, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_col(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col(None, None, 0, 128, None, None, None) == binding.OK
     assert L.mxfp4_row_to_fp8_col_grouped(a16, a16, a16, 1025, 128, 128, a16, a16, None) == binding.ERR_OFFSETS
+
+
+class _NoLaunch:
+    """Stands in for the loaded library: any entry point reached through it fails the test."""
+    def __getattr__(self, name):
+        raise AssertionError(f"{name} was reached with arguments the binding had to reject")
+
+
+@pytest.fixture
+def no_launch(monkeypatch):
+    monkeypatch.setattr(binding, "lib", lambda: _NoLaunch())
+
+
+def _t(shape, dtype=torch.uint8, device="cpu"):
+    return torch.zeros(shape, dtype=dtype, device=device)
+
+
+def test_binding_rejects_host_tensors_before_any_launch(no_launch):
+    """A tensor in host memory must never have its address handed to a kernel: every wrapper raises TypeError
+    on well-shaped CPU tensors, inputs and caller-supplied outputs alike."""
+    M, K = 128, 256
+    x, s = _t((M, K)), _t((M, K // 128), torch.float32)
+    q, sf = _t((M, K // 2)), _t((M, K // 32))
+    off = torch.tensor([0, 64, 128], dtype=torch.int32)
+    calls = [
+        lambda: mx.mxfp4_quant_from_fp8(x, s),
+        lambda: mx.mxfp4_quant_from_fp8(x, s, gather_idx=torch.zeros(4, dtype=torch.int32)),
+        lambda: mx.mxfp4_quant_from_fp8_scatter(x, s, torch.zeros((M, 2), dtype=torch.int32), 2 * M),
+        lambda: mx.mxfp4_quant_from_bf16(_t((M, K), torch.bfloat16)),
+        lambda: mx.mxfp4_dequant_to_fp8(q, sf),
+        lambda: mx.mxfp4_dequant_to_fp8(q.view(-1), sf.view(-1), M=M, K=K, ld_q=K // 2, ld_sf=K // 32),
+        lambda: mx.mxfp4_row_to_col(q, sf),
+        lambda: mx.mxfp4_quant_from_fp8_grouped(x, s, off),
+        lambda: mx.mxfp4_row_to_col_grouped(q, sf, off),
+        lambda: mx.mxfp4_row_to_fp8_col(q, sf),
+        lambda: mx.mxfp4_row_to_fp8_col(q, sf, requant=True),
+        lambda: mx.mxfp4_row_to_fp8_col_grouped(q, sf, off),
+    ]
+    for i, call in enumerate(calls):
+        with pytest.raises(TypeError, match="HIP device tensor"):
+            call()
+    with pytest.raises(TypeError):
+        mx.mxfp4_row_to_col(q.numpy(), sf)
+
+
+def test_binding_rejects_wrong_dtypes_shapes_and_short_buffers(no_launch):
+    """dtype, contiguity, exact scale shapes and the extent of every caller-supplied output are checked before
+    the device is, so the checks themselves are exercised without a GPU; nothing reaches the library."""
+    M, K = 128, 256
+    x, s = _t((M, K)), _t((M, K // 128), torch.float32)
+    q, sf = _t((M, K // 2)), _t((M, K // 32))
+    off = torch.tensor([0, 60, 128], dtype=torch.int32)
+    rec = K // 2 + K // 32
+    bad = [
+        (TypeError, lambda: mx.mxfp4_quant_from_fp8(x.to(torch.int8), s)),
+        (TypeError, lambda: mx.mxfp4_quant_from_fp8(x, s.double())),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s[:, :1])),                      # scale not contiguous
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, _t((M, 1), torch.float32))),     # wrong scale shape
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, _t((M - 1, 2), torch.float32))),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(_t((M, 100)), s)),                  # K % 128
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x.view(-1), s)),                    # not 2-D
+        (TypeError, lambda: mx.mxfp4_quant_from_fp8(x, s, gather_idx=torch.zeros(4, dtype=torch.int64))),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t((M, K // 2 - 1)))),      # short output
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, sf=_t((M - 1, K // 32)))),
+        (TypeError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t((M, K // 2), torch.int8))),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t((M, K))[:, :K // 2])),   # strided output view
+        # per-token records: the views must reach the end of the last record
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t(M * rec - K // 32 - 1), sf=_t(M * rec)[K // 2:], ld_q=rec,
+                                                     ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t(M * rec), sf=_t(M * rec)[K // 2 + 1:], ld_q=rec,
+                                                     ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, q=_t(M * rec), sf=_t(M * rec), ld_q=K // 2 - 8, ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, ld_q=rec)),                   # stride without a buffer
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8(x, s, gather_idx=torch.zeros(2 * M, dtype=torch.int32), q=q)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8_scatter(x, s, torch.zeros((M - 1, 2), dtype=torch.int32), M)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8_scatter(x, s, torch.zeros(2 * M, dtype=torch.int32), M)),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8_scatter(x, s, torch.zeros((M, 2), dtype=torch.int32), 2 * M, q=q)),
+        (TypeError, lambda: mx.mxfp4_quant_from_bf16(_t((M, K), torch.float16))),
+        (ValueError, lambda: mx.mxfp4_quant_from_bf16(_t((M, K), torch.bfloat16), sf=_t((M, K // 32 - 1)))),
+        (TypeError, lambda: mx.mxfp4_dequant_to_fp8(q.to(torch.int8), sf)),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(q, _t((M, K // 32 + 1)))),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(q, sf, x=_t((M, K - 1)))),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(q, sf, x_scale=_t((M, K // 128 - 1), torch.float32))),
+        (TypeError, lambda: mx.mxfp4_dequant_to_fp8(q, sf, x_scale=_t((M, K // 128), torch.float64))),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(q, sf, M=M)),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(_t(M * rec - K // 32 - 1), _t(M * rec)[K // 2:], M=M, K=K, ld_q=rec, ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(_t(M * rec), _t(M * rec)[K // 2:], M=M + 1, K=K, ld_q=rec, ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_dequant_to_fp8(_t(M * rec), _t(M * rec)[K // 2:], M=M, K=K + 1, ld_q=rec, ld_sf=rec)),
+        (ValueError, lambda: mx.mxfp4_row_to_col(q, _t((M, K // 32 - 1)))),
+        (ValueError, lambda: mx.mxfp4_row_to_col(q[:48], sf[:48])),                      # M % 32
+        (ValueError, lambda: mx.mxfp4_row_to_col(q, sf, q_col=_t((K, M // 2 - 1)))),
+        (ValueError, lambda: mx.mxfp4_row_to_col(q, sf, sf_col=_t((K, M // 32 - 1)))),
+        (TypeError, lambda: mx.mxfp4_row_to_col(q, sf, sf_col=_t((K, M // 32), torch.int32))),
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col(q[:96], sf[:96])),                  # M % 128
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col=_t((K, M - 1)))),
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col_scale=_t(K * M // 128 - 1, torch.float32))),
+        (TypeError, lambda: mx.mxfp4_row_to_fp8_col(q, sf, x_col_scale=_t(K * M // 128))),
+        (TypeError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off.long())),
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off[:1])),
+        # grouped outputs without host offsets need the documented upper bounds; exact sizes need the offsets
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, q_col=_t(K * M // 2), sf_col=_t(K * (M // 32 + 2)))),
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, q_col=_t(K * (M // 2 + 2)), sf_col=_t(K * M // 32))),
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, q_col=_t(K * M // 2), sf_col=_t(K * 5 - 1),
+                                                         offsets_host=[0, 60, 128])),   # ceil(60/32)+ceil(68/32) = 5
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, offsets_host=[0, 60, 127])),
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, offsets_host=[0, 130, 128])),
+        (ValueError, lambda: mx.mxfp4_row_to_col_grouped(q, sf, off, offsets_host=[0, 128])),
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col_grouped(q, sf, off, x_col=_t(M * K - 1))),
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col_grouped(q, sf, off, x_col_scale=_t(K * 2, torch.float32))),
+        (ValueError, lambda: mx.mxfp4_row_to_fp8_col_grouped(q, sf, off, x_col_scale=_t(K * 2 - 1, torch.float32),
+                                                             offsets_host=[0, 60, 128])),
+        (ValueError, lambda: mx.mxfp4_quant_from_fp8_grouped(x, s, off, q=_t((M, K // 2 - 1)))),
+    ]
+    for i, (exc, call) in enumerate(bad):
+        with pytest.raises(exc):
+            call()
+        try:
+            call()
+        except (TypeError, ValueError) as e:
+            assert "HIP device tensor" not in str(e), f"case {i} passed every check up to the device check: {e}"
+
+
+def test_binding_accepts_exact_grouped_sizes_with_host_offsets(no_launch):
+    """With the offsets also given as host integers the exact output sizes pass every size check (the call then
+    stops at the device check, these being CPU tensors)."""
+    M, K = 128, 256
+    q, sf = _t((M, K // 2)), _t((M, K // 32))
+    off = torch.tensor([0, 60, 128], dtype=torch.int32)
+    with pytest.raises(TypeError, match="HIP device tensor"):
+        mx.mxfp4_row_to_col_grouped(q, sf, off, q_col=_t(K * 64), sf_col=_t(K * 5), offsets_host=off)
+    with pytest.raises(TypeError, match="HIP device tensor"):
+        mx.mxfp4_row_to_fp8_col_grouped(q, sf, off, x_col=_t(K * M), x_col_scale=_t(K * 2, torch.float32),
+                                        offsets_host=off)
 
 
 def test_bench_refuses_more_than_one_gpu():

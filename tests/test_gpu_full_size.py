@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of the five configurations and of the benchmark workload,
 in the launch configuration bench.py times.  Outputs are compared with the CPU oracle bit
 for bit: completely where the oracle finishes in seconds (it runs over row ranges in a thread
-pool), on sampled rows plus structural properties for the 524288-row dispatch payload."""
+pool), the 524288-row dispatch payload included (65536 records at a time)."""
 import numpy as np
 import pytest
 import torch
@@ -146,21 +146,32 @@ def test_config5_dispatch_payload_round_trip(target):
     mx.mxfp4_quant_from_fp8_scatter(x8, s, dst, Mo, q=buf2, sf=buf2[K // 2:], ld_q=rec, ld_sf=rec)
     assert torch.equal(buf2, buf)
     del buf2, dst
-    # sampled rows straight against the oracle (gathered form)
+    # the oracle's own gathered form on sampled rows (the routine with the index argument)
     g = torch.Generator().manual_seed(7)
     rows = torch.randperm(Mo, generator=g)[:4096].sort().values
-    xs_h, s_h = host(x8), host(s)
-    wq, wsf = ref.quant_from_fp8(xs_h, s_h, gather_idx=host(idx)[rows.numpy()])
+    xs_h, s_h, idx_h = host(x8), host(s), host(idx)
+    wq, wsf = ref.quant_from_fp8(xs_h, s_h, gather_idx=idx_h[rows.numpy()])
     got = host(recs[rows.to(DEV)])
     assert_same(got[:, : K // 2], wq, "cfg5 sampled record nibbles")
     assert_same(got[:, K // 2:], wsf, "cfg5 sampled record scales")
-    # and back: dequantize the whole payload from the records, check sampled rows
+    # and back: dequantize the whole payload from the records
     x = torch.empty((Mo, K), dtype=torch.uint8, device=DEV)
     xsc = torch.empty((Mo, K // 128), dtype=torch.float32, device=DEV)
     mx.mxfp4_dequant_to_fp8(buf, buf[K // 2:], M=Mo, K=K, ld_q=rec, ld_sf=rec, x=x, x_scale=xsc)
-    wx, wxs = par.dequant(wq, wsf)
-    assert_same(host(x[rows.to(DEV)]), wx, "cfg5 sampled dequantized bytes")
-    assert_same(host(xsc[rows.to(DEV)]), wxs, "cfg5 sampled tile scales")
+    # ALL 524288 records and all their de-quantized rows against the oracle, 65536 records at a time: the oracle
+    # quantizes the routed rows themselves (gathered on the host) and de-quantizes its own result
+    for lo in range(0, Mo, 65536):
+        sl = slice(lo, lo + 65536)
+        src = idx_h[sl]
+        wq, wsf = par.quant(xs_h[src], s_h[src])
+        got = host(recs[sl])
+        assert_same(got[:, : K // 2], wq, f"cfg5 record nibbles, records {lo}..")
+        assert_same(got[:, K // 2:], wsf, f"cfg5 record scales, records {lo}..")
+        wx, wxs = par.dequant(wq, wsf)
+        assert_same(host(xsc[sl]), wxs, f"cfg5 de-quantized tile scales, records {lo}..")
+        assert_same(host(x[sl]), wx, f"cfg5 de-quantized bytes, records {lo}..")
+        print(f"cfg5: records {lo}..{lo + 65535} equal the oracle", flush=True)
+    del wq, wsf, wx, wxs, got
     # sizes: the closed-form payloads
     assert buf.numel() == synth.payload_bytes(Mo, K)["mxfp4"]
     assert x.numel() + 4 * xsc.numel() == synth.payload_bytes(Mo, K)["fp8"]
@@ -201,7 +212,7 @@ def test_ragged_32_experts_without_padding_65536x7168(target):
     wqc, wsc = per_expert(ref.row_to_col_grouped)
     qbuf, qv = guarded(wqc.size, torch.uint8, 0xA5)
     sbuf, sv = guarded(wsc.size, torch.uint8, 0x5A)
-    mx.mxfp4_row_to_col_grouped(q, sf, offd, q_col=qv, sf_col=sv)
+    mx.mxfp4_row_to_col_grouped(q, sf, offd, q_col=qv, sf_col=sv, offsets_host=off)
     assert_same(unguard(sbuf, wsc.size, 0x5A, "sf_col"), wsc, "ragged row->col scale bytes")
     assert_same(unguard(qbuf, wqc.size, 0xA5, "q_col"), wqc, "ragged row->col nibbles")
     del qbuf, sbuf, wqc, wsc
@@ -210,7 +221,7 @@ def test_ragged_32_experts_without_padding_65536x7168(target):
         wx, wxs = per_expert(lambda a, b, o: ref.row_to_fp8_col_grouped(a, b, o, requant=requant))
         xbuf, xv = guarded(wx.size, torch.uint8, 0xA5)
         fbuf, fv = guarded(wxs.size, torch.float32, -7.0)
-        mx.mxfp4_row_to_fp8_col_grouped(q, sf, offd, x_col=xv, x_col_scale=fv, requant=requant)
+        mx.mxfp4_row_to_fp8_col_grouped(q, sf, offd, x_col=xv, x_col_scale=fv, requant=requant, offsets_host=off)
         assert_same(unguard(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"ragged FP8 column scales, requant={requant}")
         assert_same(unguard(xbuf, wx.size, 0xA5, "x_col"), wx, f"ragged FP8 column bytes, requant={requant}")
         del xbuf, fbuf, wx, wxs

@@ -434,7 +434,8 @@ def test_row_to_fp8_col_ragged_splits_without_padding(K):
     xbuf = torch.full((guard + wx.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
     sbuf = torch.full((guard + wxs.size + guard,), -7.0, dtype=torch.float32, device=DEV)
     mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV),
-                                    x_col=xbuf[guard:guard + wx.size], x_col_scale=sbuf[guard:guard + wxs.size])
+                                    x_col=xbuf[guard:guard + wx.size], x_col_scale=sbuf[guard:guard + wxs.size],
+                                    offsets_host=off)
     xb, sb = host(xbuf), host(sbuf)
     assert (xb[:guard] == 0xA5).all() and (xb[guard + wx.size:] == 0xA5).all(), "bytes written outside x_col"
     assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
@@ -501,7 +502,7 @@ def test_row_to_fp8_col_requant_ragged_splits(K):
     xbuf = torch.full((guard + wx.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
     sbuf = torch.full((guard + wxs.size + guard,), -7.0, dtype=torch.float32, device=DEV)
     mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV), x_col=xbuf[guard:guard + wx.size],
-                                    x_col_scale=sbuf[guard:guard + wxs.size], requant=True)
+                                    x_col_scale=sbuf[guard:guard + wxs.size], requant=True, offsets_host=off)
     xb, sb = host(xbuf), host(sbuf)
     assert (xb[:guard] == 0xA5).all() and (xb[guard + wx.size:] == 0xA5).all(), "bytes written outside x_col"
     assert (sb[:guard] == -7.0).all() and (sb[guard + wxs.size:] == -7.0).all(), "floats written outside x_col_scale"
@@ -603,7 +604,7 @@ def test_row_to_col_ragged_splits_without_padding(K):
     qbuf = torch.full((guard + wqc.size + guard,), 0xA5, dtype=torch.uint8, device=DEV)
     sbuf = torch.full((guard + wsc.size + guard,), 0x5A, dtype=torch.uint8, device=DEV)
     mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), torch.from_numpy(off).to(DEV), q_col=qbuf[guard:guard + wqc.size],
-                                sf_col=sbuf[guard:guard + wsc.size])
+                                sf_col=sbuf[guard:guard + wsc.size], offsets_host=off)
     qb, sb = host(qbuf), host(sbuf)
     assert (qb[:guard] == 0xA5).all() and (qb[guard + wqc.size:] == 0xA5).all(), "bytes written outside q_col"
     assert (sb[:guard] == 0x5A).all() and (sb[guard + wsc.size:] == 0x5A).all(), "bytes written outside sf_col"

@@ -99,7 +99,7 @@ def test_grouped_entry_points_on_random_splits(seed):
     wqc, wsc = ref.row_to_col_grouped(q, sf, off)
     qbuf, qv = guarded(wqc.size, torch.uint8, 0xA5)
     sbuf, sv = guarded(wsc.size, torch.uint8, 0x5A)
-    mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd, q_col=qv, sf_col=sv)
+    mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd, q_col=qv, sf_col=sv, offsets_host=off)
     same(check_guards(sbuf, wsc.size, 0x5A, "sf_col"), wsc, f"grouped row->col scales T={T} K={K}")
     same(check_guards(qbuf, wqc.size, 0xA5, "q_col"), wqc, f"grouped row->col nibbles T={T} K={K}")
 
@@ -107,7 +107,7 @@ def test_grouped_entry_points_on_random_splits(seed):
         wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off, requant=requant)
         xbuf, xv = guarded(wx.size, torch.uint8, 0xA5)
         fbuf, fv = guarded(wxs.size, torch.float32, -7.0)
-        mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, x_col=xv, x_col_scale=fv, requant=requant)
+        mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, x_col=xv, x_col_scale=fv, requant=requant, offsets_host=off)
         same(check_guards(fbuf, wxs.size, -7.0, "x_col_scale"), wxs, f"grouped FP8 col scales T={T} K={K} requant={requant}")
         same(check_guards(xbuf, wx.size, 0xA5, "x_col"), wx, f"grouped FP8 col bytes T={T} K={K} requant={requant}")
 
