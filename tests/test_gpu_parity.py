@@ -236,16 +236,18 @@ def test_empty_and_argument_errors():
     assert q.shape == (0, 128) and sf.shape == (0, 8)
     x8 = torch.zeros((32, 256), dtype=torch.uint8, device=DEV)
     xs = torch.ones((32, 2), dtype=torch.float32, device=DEV)
-    with pytest.raises(mx.Mxfp4Error) as e:
-        mx.mxfp4_quant_from_fp8(x8[:, :192].contiguous(), xs)          # K % 128 != 0
-    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        mx.mxfp4_quant_from_fp8(x8[:, :192].contiguous(), xs)          # K % 128 != 0: stopped by the binding
     with pytest.raises(mx.Mxfp4Error) as e:
         mx.mxfp4_quant_from_fp8(x8.reshape(-1)[1:257].reshape(1, 256), xs[:1])   # misaligned
     assert e.value.status == -3
     q, sf = mx.mxfp4_quant_from_fp8(x8, xs)
-    with pytest.raises(mx.Mxfp4Error) as e:
-        mx.mxfp4_row_to_col(q[:16], sf[:16])                            # M % 32 != 0
-    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        mx.mxfp4_row_to_col(q[:16], sf[:16])                            # M % 32 != 0: stopped by the binding
+    with pytest.raises(TypeError):
+        mx.mxfp4_row_to_col(q, sf, q_col=torch.empty((256, 16), dtype=torch.uint8))   # an output in host memory
+    with pytest.raises(ValueError):
+        mx.mxfp4_row_to_col(q, sf, sf_col=torch.empty((256, 1), dtype=torch.uint8, device=DEV)[:255])
 
 
 # ------------------------------------------------------------------ BF16 -> MXFP4 (the paper's row-wise kernel)
@@ -360,9 +362,8 @@ def test_row_to_fp8_col_empty_and_argument_errors():
     assert x.shape == (256, 0) and xs.shape == (256, 0)
     q = torch.zeros((96, 128), dtype=torch.uint8, device=DEV)
     sf = torch.zeros((96, 8), dtype=torch.uint8, device=DEV)
-    with pytest.raises(mx.Mxfp4Error) as e:
-        mx.mxfp4_row_to_fp8_col(q, sf)                                  # M % 128 != 0
-    assert e.value.status == -2
+    with pytest.raises(ValueError):
+        mx.mxfp4_row_to_fp8_col(q, sf)                                  # M % 128 != 0: stopped by the binding
     q = torch.zeros((128, 128), dtype=torch.uint8, device=DEV)
     sf = torch.zeros((128, 8), dtype=torch.uint8, device=DEV)
     xbuf = torch.zeros(256 * 128 + 16, dtype=torch.uint8, device=DEV)
