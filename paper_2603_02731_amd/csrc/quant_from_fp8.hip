@@ -36,7 +36,7 @@ constexpr int QUANT_UNROLL = MXFP4_QUANT_UNROLL;
 #define MXFP4_QUANT_NT_LOAD 1
 #endif
 #ifndef MXFP4_QUANT_NT_STORE
-#define MXFP4_QUANT_NT_STORE 0
+#define MXFP4_QUANT_NT_STORE 1
 #endif
 
 // Gathered form (top-8 payload of 65536 tokens), policies fixed at compile time per kernel instance: plain loads

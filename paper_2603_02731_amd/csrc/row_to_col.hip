@@ -443,7 +443,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
             if (have == 16u && aligned16) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
-                    *reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q) = s_out[u * T_THREADS + tid];
+                    __builtin_nontemporal_store(s_out[u * T_THREADS + tid], reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q));
             } else if (have == 16u) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
