@@ -20,37 +20,16 @@
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
-// Cache policy, measured inside the three-kernel step at [65536,7168]: non-temporal both ways
-// 116 us; plain stores 122 us; plain loads 112 us here but 13 us more in the kernels around it.
-#ifndef MXFP4_DEQUANT_NT_LOAD
-#define MXFP4_DEQUANT_NT_LOAD 1
-#endif
-// The E4M3 bytes, two thirds of the kernel's traffic and written in address order by the whole grid, leave
-// with streaming stores (store_streaming: 116.7 -> 108.6 us at [65536,7168] against the non-temporal hint
-// alone; with the nibbles coming from HBM instead of the cache: 120-123 -> 120 us).  The 4-byte tile scales must
-// not: 146 us with them streamed.
-#ifndef MXFP4_DEQUANT_STREAM_STORE
-#define MXFP4_DEQUANT_STREAM_STORE 1
-#endif
-#ifndef MXFP4_DEQUANT_NT_STORE
-#define MXFP4_DEQUANT_NT_STORE 1
-#endif
-
 namespace mxfp4 {
 
-// 128 lanes x 2 runs per workgroup.  Measured at [65536,7168] with the streaming stores, inside the step (where
-// the nibbles were written by the kernel before and still sit in the memory-side cache) / launched on its own
-// after a 470 MB copy (nibbles from HBM): 128 x 2 103.0 / 119 us, 256 x 2 107.4 / 118.5, 512 x 2 111.4 / 119.5,
-// 1024 x 1 103.1 / 135, 512 x 1 104.2 / 122, 256 x 1 105.6 / 125, 128 x 4 117.5 / 124, 64 x 4 106.6 / 124.
-// One load in flight per lane is enough when the input comes from the cache and not when it comes from memory.
-#ifndef MXFP4_DEQUANT_THREADS
-#define MXFP4_DEQUANT_THREADS 128
-#endif
-constexpr int DEQUANT_THREADS = MXFP4_DEQUANT_THREADS;
-#ifndef MXFP4_DEQUANT_UNROLL
-#define MXFP4_DEQUANT_UNROLL 2
-#endif
-constexpr int DEQUANT_UNROLL = MXFP4_DEQUANT_UNROLL;
+// Cache policy and launch shape, measured at [65536,7168] over rotated buffer sets (every byte from and to HBM).
+// Non-temporal loads; the E4M3 bytes, two thirds of the traffic and written in address order by the whole grid,
+// leave with streaming stores (store_streaming): 111 us, against 115 us with the non-temporal hint alone and
+// 114 us with plain loads.  The 4-byte tile scales must not be streamed (146 us).  128 lanes x 2 runs per
+// workgroup: 256 x 2 111.4, 512 x 2 112.1, 128 x 4 117, 256 x 4 119, 1024 x 1 129 us (one load in flight per lane
+// is not enough when the nibbles come from memory).
+constexpr int DEQUANT_THREADS = 128;
+constexpr int DEQUANT_UNROLL = 2;
 
 // E4M3 magnitude byte of e2m1(code) * 2^(6-d) for d in [12, 19], rounded to nearest-even.
 // e2m1(code) = h/2 with h below; in units of the E4M3 subnormal quantum 2^-9 the value is
@@ -138,11 +117,7 @@ __global__ void __launch_bounds__(DEQUANT_THREADS) dequant_to_fp8_kernel(const D
             src = a.q + (size_t)row * a.ld_q + (size_t)ch * 8;
             src_sf = a.sf + (size_t)row * a.ld_sf + (ch >> 1);
         }
-#if MXFP4_DEQUANT_NT_LOAD
         w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
-#else
-        w[u] = *reinterpret_cast<const u32x2 *>(src);
-#endif
         sfb[u] = *src_sf;
     }
 
@@ -192,15 +167,7 @@ __global__ void __launch_bounds__(DEQUANT_THREADS) dequant_to_fp8_kernel(const D
             o[2 * j] = perm(odd, even, 0x05010400u);     // elements 0..3 of this dword
             o[2 * j + 1] = perm(odd, even, 0x07030602u); // elements 4..7
         }
-#if MXFP4_DEQUANT_NT_STORE
-#if MXFP4_DEQUANT_STREAM_STORE
         store_streaming(a.x + (size_t)c * 16, o);
-#else
-        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(a.x + (size_t)c * 16));
-#endif
-#else
-        *reinterpret_cast<u32x4 *>(a.x + (size_t)c * 16) = o;
-#endif
 
         if ((threadIdx.x & 7u) == 0u) {
             // 2^(bmax - 6 - 127): the byte goes straight into the FP32 exponent field; below

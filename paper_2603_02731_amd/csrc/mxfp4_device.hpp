@@ -106,7 +106,7 @@ __device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
 // and their few-byte scale pieces complete whole lines in that L2) and along k (they share the
 // 32-byte sectors of the row scales).  Returns false for the ids that round the grid up.
 constexpr uint32_t NUM_XCD = 8;
-template <uint32_t MBM, uint32_t MBK, bool K_FASTEST = false>
+template <uint32_t MBM, uint32_t MBK>
 __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
                                                   uint32_t *tile_m, uint32_t *tile_k)
 {
@@ -121,16 +121,9 @@ __device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m,
     const uint32_t mb_rows = min(MBM, tiles_m - mg * MBM);
     const uint32_t kg = rem / (MBK * mb_rows);
     const uint32_t rem2 = rem - kg * MBK * mb_rows;
-    if (K_FASTEST) { // inside a macro block walk k first
-        const uint32_t kw = min(MBK, tiles_k - kg * MBK);
-        const uint32_t m_in = rem2 / kw;
-        *tile_m = mg * MBM + m_in;
-        *tile_k = kg * MBK + (rem2 - m_in * kw);
-    } else {
-        const uint32_t k_in = rem2 / mb_rows;
-        *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
-        *tile_k = kg * MBK + k_in;
-    }
+    const uint32_t k_in = rem2 / mb_rows;
+    *tile_m = mg * MBM + (rem2 - k_in * mb_rows);
+    *tile_k = kg * MBK + k_in;
     return true;
 }
 
@@ -160,7 +153,7 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 // `a_before` / `b_before` the sum of ceil(T_j / UNIT) over the experts before it (where its
 // outputs start when the splits are not padded).
 constexpr int MAX_EXPERT_CHUNKS = 16; // 64 experts each: MXFP4_MAX_EXPERTS of the C ABI
-template <uint32_t TILE_ROWS, uint32_t UNIT_A, uint32_t UNIT_B, uint32_t MBM, uint32_t MBK, bool K_FASTEST = false>
+template <uint32_t TILE_ROWS, uint32_t UNIT_A, uint32_t UNIT_B, uint32_t MBM, uint32_t MBK>
 __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, int32_t num_experts, uint32_t id,
                                                           uint32_t tiles_k, uint32_t *tile_m, uint32_t *tile_k,
                                                           uint32_t *row_base, uint32_t *rows,
@@ -190,7 +183,7 @@ __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, in
         total += (uint32_t)__builtin_amdgcn_readlane((int)incl[c], 63);
     }
     uint32_t tile;
-    if (!tile_of_workgroup<MBM, MBK, K_FASTEST>(id, total, tiles_k, &tile, tile_k))
+    if (!tile_of_workgroup<MBM, MBK>(id, total, tiles_k, &tile, tile_k))
         return false;
 
     uint32_t before = 0, abefore = 0, bbefore = 0; // tiles / units of the experts in earlier chunks
@@ -228,10 +221,11 @@ __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, in
 
 // Streaming stores for outputs that this kernel does not read again: the non-temporal hint together
 // with the sc1 bit of the gfx940-family vector stores (the write goes through at device scope
-// instead of waiting in the L2 for an eviction).  Measured at [65536,7168] inside a three-kernel
-// step: the 16-byte E4M3 stores of the de-quantizer 116.7 -> 108.6 us against the non-temporal
-// hint alone; sc1 without the hint is slower than either (119 us, and the kernels that follow
-// lose 10 %).  The builtin non-temporal store only sets the hint, hence the asm.
+// instead of waiting in the L2 for an eviction).  Measured at [65536,7168] with every byte going to HBM:
+// the 16-byte E4M3 stores of the de-quantizer, written in address order by the whole grid, 115 -> 111 us
+// against the non-temporal hint alone.  Where neighbouring workgroups complete each other's lines (the
+// transposed rows of row_to_col: 93 -> 97 us) or the pieces are small, the hint alone is the better form.
+// The builtin non-temporal store only sets the hint, hence the asm.
 __device__ __forceinline__ void store_streaming(void *p, u32x4 v)
 {
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");

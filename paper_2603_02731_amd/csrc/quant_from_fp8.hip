@@ -17,41 +17,16 @@
 
 namespace mxfp4 {
 
-// Lanes per workgroup (each lane takes QUANT_UNROLL chunks).  Dense rows: 512 x 2 runs, 111.0 us at [65536,7168]
-// inside the step against 112.6 with 256 x 2, 116.2 with 1024 x 2, 118.9 with 512 x 1 and 128.7 with 1024 x 1.
-// Gathered, strided and scattered rows: 256 (top-8 gather 1015 us against 1035 with 512, records 1041 against
-// 1056, scatter 462 against 466).
-#ifndef MXFP4_QUANT_THREADS
-#define MXFP4_QUANT_THREADS 512
-#endif
-constexpr int QUANT_THREADS = MXFP4_QUANT_THREADS; // dense rows
-constexpr int QUANT_THREADS_ROUTED = 256;          // gathered, strided, scattered rows
-#ifndef MXFP4_QUANT_UNROLL
-#define MXFP4_QUANT_UNROLL 2
-#endif
-constexpr int QUANT_UNROLL = MXFP4_QUANT_UNROLL;
-// Cache policy, measured inside the three-kernel step at [65536,7168]: non-temporal loads with
-// plain stores 112 us; non-temporal both ways 117 us; plain both ways 134 us.
-#ifndef MXFP4_QUANT_NT_LOAD
-#define MXFP4_QUANT_NT_LOAD 1
-#endif
-#ifndef MXFP4_QUANT_NT_STORE
-#define MXFP4_QUANT_NT_STORE 1
-#endif
-
-// Gathered form (top-8 payload of 65536 tokens), policies fixed at compile time per kernel instance: plain loads
-// with non-temporal stores 1012 us, plain loads with plain stores 1090 us, non-temporal loads with plain
-// stores 1130 us.
-#ifndef MXFP4_GATHER_NT_LOAD
-#define MXFP4_GATHER_NT_LOAD 0
-#endif
-#ifndef MXFP4_GATHER_NT_STORE
-#define MXFP4_GATHER_NT_STORE 1
-#endif
-// Scatter form: non-temporal stores of the packed rows 463 us at 65536 tokens x top-8, plain stores 645 us.
-#ifndef MXFP4_SCATTER_NT_STORE
-#define MXFP4_SCATTER_NT_STORE 1
-#endif
+// Lanes per workgroup (each lane takes QUANT_UNROLL chunks).  Dense rows: 512 x 2 runs; at [65536,7168] over
+// rotated buffers 256 x 2 and 256 x 4 are as fast, 1024 x 2 is 5 % slower.  Gathered, strided and scattered rows: 256.
+constexpr int QUANT_THREADS = 512;        // dense rows
+constexpr int QUANT_THREADS_ROUTED = 256; // gathered, strided, scattered rows
+constexpr int QUANT_UNROLL = 2;
+// Cache policy, measured at [65536,7168] over rotated buffer sets (every byte from and to HBM): non-temporal
+// loads and stores 109 us; non-temporal loads with plain stores 118 us (that form is the faster one, 104 against
+// 107 us, only when the 250 MB of output are rewritten in place and stay in the memory-side cache); plain
+// loads 121 us.  Gathered rows are read several times: plain loads with non-temporal stores 1012 us for the
+// top-8 payload of 65536 tokens, plain both ways 1090 us, non-temporal loads with plain stores 1130 us.
 
 struct QuantArgs {
     const uint8_t *x;
@@ -150,14 +125,10 @@ __global__ void __launch_bounds__(THREADS) quant_from_fp8_kernel(const QuantArgs
             dst_q[u] = a.q + (size_t)row * a.ld_q + (size_t)cc * 8;
             dst_sf[u] = a.sf + (size_t)row * a.ld_sf + (size_t)(cc >> 3) * 4;
         }
-#if MXFP4_QUANT_NT_LOAD
-        if (!GATHER || MXFP4_GATHER_NT_LOAD)
+        if (!GATHER)
             w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
         else
             w[u] = *reinterpret_cast<const u32x4 *>(src); // gathered rows are read several times
-#else
-        w[u] = *reinterpret_cast<const u32x4 *>(src);
-#endif
         s[u] = *src_scale;
         if (!valid) { // an out-of-range gather index yields a zero row
             w[u] = u32x4{0u, 0u, 0u, 0u};
@@ -171,12 +142,7 @@ __global__ void __launch_bounds__(THREADS) quant_from_fp8_kernel(const QuantArgs
             break;
         uint32_t out[2], b;
         quant16(w[u], s[u], out, &b);
-        // the dense output is read by the next kernel of a step; a gathered payload (several times the
-        // source) is not, and streaming it leaves the caches to the rows that are read again
-        if (MXFP4_QUANT_NT_STORE || (GATHER && MXFP4_GATHER_NT_STORE))
-            __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
-        else
-            *reinterpret_cast<u32x2 *>(dst_q[u]) = u32x2{out[0], out[1]};
+        __builtin_nontemporal_store(u32x2{out[0], out[1]}, reinterpret_cast<u32x2 *>(dst_q[u]));
 
         // lanes 2j, 2j+1 of the tile's 8 hold block j's byte: gather the four into lane 0
         uint32_t t = b | (dpp_read<DPP_QUAD_XOR2>(b) << 8); // lanes 0,1: B0 | B1 << 8
@@ -244,12 +210,8 @@ __global__ void __launch_bounds__(QUANT_THREADS_ROUTED) quant_from_fp8_scatter_k
             for (int j = 0; j < 8; ++j) {
                 if (d[j] >= a.M_out) // also skips negative entries and the tail of the batch
                     continue;
-#if MXFP4_SCATTER_NT_STORE
                 __builtin_nontemporal_store(u32x2{out[0], out[1]},
                                             reinterpret_cast<u32x2 *>(a.q + (size_t)d[j] * a.ld_q + (size_t)cc * 8));
-#else
-                *reinterpret_cast<u32x2 *>(a.q + (size_t)d[j] * a.ld_q + (size_t)cc * 8) = u32x2{out[0], out[1]};
-#endif
                 if ((threadIdx.x & 7u) == 0u)
                     *reinterpret_cast<uint32_t *>(a.sf + (size_t)d[j] * a.ld_sf + (size_t)(cc >> 3) * 4) = t;
             }

@@ -26,30 +26,12 @@
 
 namespace mxfp4 {
 
-// store_streaming for the 128-byte output rows: 90.5 -> 100.8 us at [65536,7168] (the non-temporal hint
-// alone: +5 %), so they are plain stores.
-#ifndef MXFP4_RTC_NRG
-#define MXFP4_RTC_NRG 8
-#endif
-#ifndef MXFP4_RTC_MBM
-#define MXFP4_RTC_MBM 32
-#endif
-#ifndef MXFP4_RTC_MBK
-#define MXFP4_RTC_MBK 4
-#endif
-#ifndef MXFP4_RTC_WAVES
-#define MXFP4_RTC_WAVES 1
-#endif
-constexpr int NRG = MXFP4_RTC_NRG;  // 32-row groups per tile
+constexpr int NRG = 8;              // 32-row groups per tile
 constexpr int T_THREADS = 32 * NRG; // one lane per (row group, 8-column group)
 constexpr int TILE_M = 32 * NRG;
 constexpr int TILE_K = 256;
-#ifndef MXFP4_RTC_SFPAD
-#define MXFP4_RTC_SFPAD 16
-#endif
 // row scales of one k-block in LDS; the pad spreads the k-blocks over the banks
-constexpr int SF_STRIDE = TILE_M + MXFP4_RTC_SFPAD;
-static_assert(NRG == 8, "the LDS slot swizzle and the copy-out assume 8 row groups");
+constexpr int SF_STRIDE = TILE_M + 16;
 
 struct RowToColArgs {
     const uint8_t *q_row;
@@ -65,22 +47,14 @@ struct RowToColArgs {
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
 };
 
-constexpr uint32_t MBM = MXFP4_RTC_MBM, MBK = MXFP4_RTC_MBK; // macro block of the tile order
+// Macro block of the tile order: 32 row tiles (the CUs of an XCD) x 4 column tiles.  Over rotated buffers at
+// [65536,7168]: 8 / 16 / 64 row tiles 103 / 108 / 98 us against 93; 1, 2, 7, 14 or 28 column tiles no difference.
+constexpr uint32_t MBM = 32, MBK = 4;
 
-// The nibbles are read once: non-temporal loads (plain loads: 109 us against 94 at [65536,7168]).
-#ifndef MXFP4_RTC_STAGE_IN
-#define MXFP4_RTC_STAGE_IN 1
-#endif
-#ifndef MXFP4_RTC_NT_LOAD
-#define MXFP4_RTC_NT_LOAD 1
-#endif
+// The nibbles are read once: non-temporal loads.
 __device__ __forceinline__ uint32_t load_nibbles(const uint32_t *p)
 {
-#if MXFP4_RTC_NT_LOAD
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 
 // One lane's 32x8 slice through the hardware conversions.  Exact while every value
@@ -200,34 +174,35 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
     return col_bytes;
 }
 
-// One tile per workgroup and two barriers: the column scales get their own 2 KiB of LDS, so that
-// after the conversion the scale bytes and the nibbles leave without further synchronisation
-// (measured at [65536,7168]: 93 us against 98 us with the scales staged over the tile buffer
-// behind two more barriers).  Also measured and not built: walking 2/4/8 row tiles per workgroup
-// with one column-scale request per k-row (94-97 / 113 / 130 us: fewer, longer workgroups
-// overlap worse than the saved requests gain), 512-row tiles (100 us, with or without
-// non-temporal stores), non-temporal stores for the 128-byte output rows (97 us), requesting the
-// row scales before the nibbles (no difference).
-// The scale bytes sit in LDS so that no access piles up on one bank: the k-blocks of the row
-// scales are SF_STRIDE = 272 bytes apart (the eight 32-byte reads of a wave fall on different
-// banks), and the byte of column cg*8 + c goes to slot c*32 + cg, which lane tid reads back
-// linearly (94-95 -> 92-93 us; with slot k = cg*8 + c the eight byte writes of a lane met
-// 16-way conflicts, 70 % of the kernel's LDS cycles).
-// A tile copy with the same loads, stores and LDS traffic but no arithmetic takes 88 us, and 81 us
-// when the nibbles arrive through 16-byte loads.  No form of wider loads paid here, each measured
-// bit-identical to this kernel and against it in the same run (89.7 us launched back to back):
-// 16-byte loads straight into LDS (global_load_lds_dwordx4, extra barrier, 32 LDS reads per lane:
-// 89.1 us), through registers into LDS (87.5 us at this shape, but 6 % slower at [16384,2048] and
-// [4096,7168] and no faster at [262144,2048]), a lane owning 8 rows x 32 columns and combining the
-// column maxima across four lanes (v_permlane16_swap, row_ror:8; 87.7 us alone, no gain inside the
-// step), 8-byte loads with the lanes of a pair on alternate rows and a DPP exchange of the halves
-// (98 us: adjacent lanes on different rows coalesce badly).  Nor did workgroups that stay resident
-// and walk several k-tiles with the next tile's loads in flight during the conversion (3 or 4 per
-// CU, 100-104 us): the loads only enter the memory pipeline as fast as it drains, so a wave that
-// issues them early waits at the issue instead.  Storing 8 consecutive k-rows per instruction
-// instead of every 8th: 93 us.  Macro blocks of 8/16/64/128 row tiles: 95-109 us (32 = the CUs of
-// an XCD); the kernel without its arithmetic: 89.4 us.
-__global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(const RowToColArgs a)
+// One tile per workgroup and two barriers (three when the nibbles are re-sliced through LDS): the column
+// scales get their own 2 KiB of LDS, so that after the conversion the scale bytes and the nibbles leave without
+// further synchronisation.  The scale bytes sit in LDS so that no access piles up on one bank: the k-blocks of the
+// row scales are SF_STRIDE = 272 bytes apart (the eight 32-byte reads of a wave fall on different banks), and the
+// byte of column cg*8 + c goes to slot c*32 + cg, which lane tid reads back linearly (with slot k = cg*8 + c the
+// eight byte writes of a lane met 16-way conflicts, 70 % of the kernel's LDS cycles).
+//
+// What bounds it, measured at [65536,7168] over three rotated buffer sets, so that every byte comes from and
+// goes to HBM and not the 256 MB memory-side cache (93 us = 5.4 TB/s as built; all forms below bit-identical to
+// it unless they leave something out):
+//  * A kernel that only moves the nibbles in this access pattern (the same 16-byte loads of 256 x 128-byte rows,
+//    one barrier, the same 256 transposed 128-byte k-rows out, no LDS tile, no arithmetic, no scales): 79 us.
+//    This kernel without its scale traffic: 83 us; with both scale planes in a layout where a tile's 2 KiB are
+//    contiguous: 86 us.  So the scale planes, 6 % of the bytes, cost 10 us as they are laid out (8 bytes per row
+//    and per k-row: 40 % of the requests to the L2), 3 us would be their share.  Without the column-scale
+//    stores 88 us, without the row-scale loads 90 us.  Merging the pieces of four tiles into one 32-byte request
+//    gained 3.7 us on the loads and nothing on the stores; row scales through scalar loads (one 8-byte
+//    s_load per row, dealt to the lanes with v_writelane): 94-97 us.
+//  * Plain instead of non-temporal stores for the k-rows: 104 us (they only pay when the output is rewritten
+//    in place and stays in the cache: 89 against 93 us); write-through (sc1, sc0 sc1): 103 us; non-temporal
+//    column-scale stores: 142 us; non-temporal row-scale loads: 128 us.
+//  * Workgroups that stay resident and take one tile after the other lose 10 % whatever they do between the
+//    tiles, the bare copy included (79 -> 87 us with 4 per CU, by a fixed stride or by claiming tile numbers from
+//    a counter in global memory); this kernel in that form 104-110 us, also with a fifth wave that does nothing
+//    but move finished tiles from LDS to memory so that the converting waves never wait for a store.  The
+//    hardware's own dispatch of one short workgroup per tile is the better scheduler here.
+//  * Macro blocks of 8 / 16 / 64 row tiles: 103 / 108 / 98 us; 1 to 28 column tiles: no difference.  Dword loads
+//    (one per row and lane) instead of the 16-byte loads re-sliced through LDS: 95 us.
+__global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArgs a)
 {
     __shared__ u32x4 s_out[TILE_K * NRG];                // [c*32 + cg][slot]: 256 k-rows x 128 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * SF_STRIDE]; // [k-block of the tile][row]
@@ -309,9 +284,8 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
     };
     // With many tiles per CU a full tile arrives through 16-byte loads (8 rows x 128 bytes per wave
     // instruction instead of 2) and is cut into the lanes' 32 x 8 slices through the tile buffer: a wave
-    // fetches the 64 rows of its own two row groups, row-major.  At [65536,7168] 87.5 us against 89.7 launched
-    // back to back and 1.3 us less inside a three-kernel step; with few tiles per CU the extra barrier and
-    // LDS round trip cost 6 %, so the launcher asks for it only on large flat grids.
+    // fetches the 64 rows of its own two row groups, row-major.  At [65536,7168] 93 us against 95; with few
+    // tiles per CU the extra barrier and LDS round trip cost 6 %, so the launcher asks for it only on large grids.
     const bool staged = a.stage_in != 0u && n_rows == (uint32_t)TILE_M && cols == (uint32_t)TILE_K &&
                         (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
     u32x4 stage_v[8];
@@ -438,9 +412,14 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_RTC_WAVES) row_to_col_kernel(
         // bytes of this lane's 16 (= 32 rows) that exist: fewer at the ragged end of a split, where
         // k-rows also start at any byte (global memory takes unaligned vector stores)
         const uint32_t have = part * 32u < n_rows ? min(16u, (n_rows - part * 32u + 1u) / 2u) : 0u;
-        const bool aligned16 = ((reinterpret_cast<uintptr_t>(out_q) | pitch_q) & 15u) == 0u;
+        // Non-temporal stores where a tile's 128-byte piece of a k-row consists of whole 64-byte segments (over
+        // rotated buffers at [65536,7168]: 93 us against 104 with plain stores).  Where the pitch of a split
+        // puts the pieces across segment boundaries the halves of a segment come from two workgroups and have to
+        // meet in the L2 first: plain stores (32 splits of 1984 rows, pitch 992 bytes: 2.7 ns per row
+        // non-temporal, 1.7 plain).
+        const bool segments64 = ((reinterpret_cast<uintptr_t>(out_q) | pitch_q) & 63u) == 0u;
         if (cgx * 8u < cols && have != 0u) {
-            if (have == 16u && aligned16) {
+            if (have == 16u && segments64) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
                     __builtin_nontemporal_store(s_out[u * T_THREADS + tid], reinterpret_cast<u32x4 *>(dst + (size_t)u * pitch_q));
@@ -474,8 +453,8 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    // one group of rows and at least 8 tiles per CU of an MI355X (per-expert splits: 1-2 % slower with it)
-    a.stage_in = !expert_offsets && total >= 8u * 256u && MXFP4_RTC_STAGE_IN ? 1u : 0u;
+    // at least 8 tiles per CU of an MI355X
+    a.stage_in = total >= 8u * 256u ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();

@@ -25,47 +25,19 @@
 
 namespace mxfp4 {
 
-#ifndef MXFP4_F8C_RPL
-#define MXFP4_F8C_RPL 32
-#endif
-#ifndef MXFP4_F8C_PHASES
-#define MXFP4_F8C_PHASES 1
-#endif
-// macro block of the tile order: 16 x 4 tiles (32 x 4 is as fast on one big matrix, 16 x 4 is
-// 4-5 % faster on experts of 2048 or 4096 rows, whose row tiles then fill whole macro blocks)
-#ifndef MXFP4_F8C_MBM
-#define MXFP4_F8C_MBM 16
-#endif
-#ifndef MXFP4_F8C_MBK
-#define MXFP4_F8C_MBK 4
-#endif
-#ifndef MXFP4_F8C_KFAST
-#define MXFP4_F8C_KFAST 0
-#endif
-#ifndef MXFP4_F8C_WAVES
-#define MXFP4_F8C_WAVES 1
-#endif
-#ifndef MXFP4_F8C_STAGE_IN
-#define MXFP4_F8C_STAGE_IN 1
-#endif
-#ifndef MXFP4_F8C_NT
-#define MXFP4_F8C_NT 1
-#endif
-
+// Macro block of the tile order: 16 x 4 tiles (32 x 4 is as fast on one big matrix, 16 x 4 is 4-5 % faster on
+// experts of 2048 or 4096 rows, whose row tiles then fill whole macro blocks; 8 x 4: 165 us against 127 at
+// [65536,7168]; 2 or 8 k-tiles: no difference).  Measured and not built: a lane owning 16 rows with 512 lanes per
+// tile (142 us), the tile leaving in 2 or 4 LDS passes for more workgroups per CU (146-162 us), k-fastest tile order
+// (144 us), plain instead of non-temporal stores for the 256-byte output rows (145 us over rotated buffers).
 namespace fp8col {
 
-constexpr int RPL = MXFP4_F8C_RPL;       // rows of a lane's slice: 32, or 16 for twice the lanes per tile
+constexpr uint32_t MBM = 16, MBK = 4; // macro block of the tile order
+constexpr int RPL = 32;              // rows of a lane's slice
 constexpr int TILE_M = 256;
 constexpr int TILE_K = 256;
-constexpr int LRG = TILE_M / RPL;        // lane row groups per tile
-constexpr int T_THREADS = 32 * LRG;      // one lane per (row group, 8-column group)
-constexpr int PARTS = T_THREADS / 256;   // threads per row while staging the row scales
-constexpr int KBT = 8 / PARTS;           // k-blocks a thread stages
-constexpr int SPL = RPL / 16;            // 16-byte output slots of a lane per column
-constexpr int PHASES = MXFP4_F8C_PHASES; // the tile leaves in PHASES parts of 8/PHASES columns per lane
-constexpr int CP = 8 / PHASES;           // columns of a lane per phase
-static_assert(RPL == 16 || RPL == 32, "a lane owns one or two 16-byte output slots per column");
-static_assert(PHASES == 1 || PHASES == 2 || PHASES == 4, "a phase is a whole number of nibble bytes");
+constexpr int T_THREADS = 32 * (TILE_M / RPL); // one lane per (row group, 8-column group)
+constexpr int SPL = RPL / 16;        // 16-byte output slots of a lane per column
 
 struct Args {
     const uint8_t *q_row;
@@ -103,9 +75,9 @@ __device__ __forceinline__ uint32_t max_of_8_bytes(const uint8_t *p)
 
 using namespace fp8col;
 
-__global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_kernel(const Args a)
+__global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_kernel(const Args a)
 {
-    __shared__ u32x4 s_out[(TILE_K / PHASES) * 16];      // [c'*32 + cg][16 slots]: k-rows of 256 B
+    __shared__ u32x4 s_out[TILE_K * 16];                 // [c*32 + cg][16 slots]: k-rows of 256 B
     __shared__ alignas(16) uint8_t s_row_sf[8 * TILE_M]; // [k-block of the tile][row]
     __shared__ alignas(8) uint8_t s_max16[8 * 16];       // [k-block][16-row group]: max of the non-NaN bytes
     __shared__ uint8_t s_nan[4 * 8];                     // [64-row group][k-block]: a NaN scale byte occurs
@@ -115,12 +87,10 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     uint32_t tile_m, tile_k;
     uint32_t row_base = 0, rows = a.M, groups_before = 0;
     if (a.expert_offsets) {
-        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(
-                a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k, &tile_m, &tile_k, &row_base, &rows,
-                &groups_before))
+        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, MBM, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+                                                                 &tile_m, &tile_k, &row_base, &rows, &groups_before))
             return;
-    } else if (!tile_of_workgroup<MXFP4_F8C_MBM, MXFP4_F8C_MBK, MXFP4_F8C_KFAST != 0>(blockIdx.x, a.tiles_m, a.tiles_k,
-                                                                                     &tile_m, &tile_k)) {
+    } else if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k)) {
         return;
     }
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
@@ -149,7 +119,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     // On grids with many tiles per CU (flat or per-expert) a full tile arrives through 16-byte loads (8 rows x 128 bytes per
     // wave instruction instead of 2) and is cut into the lanes' slices through the tile buffer, behind one
     // more barrier: 133.6 -> 127.0 us at [65536,7168] launched back to back, 200 -> 190 us over 32 un-padded experts.
-    const bool staged = RPL == 32 && PHASES == 1 && a.stage_in != 0u && n_rows == (uint32_t)TILE_M &&
+    const bool staged = a.stage_in != 0u && n_rows == (uint32_t)TILE_M &&
                         cols == (uint32_t)TILE_K && (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
     u32x4 stage_v[8];
     if (staged) {
@@ -178,31 +148,27 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         }
     }
 
-    // ---- stage the tile's row scales (PARTS threads per row, KBT bytes each) and reduce them:
+    // ---- stage the tile's row scales (thread t takes row t, 8 bytes) and reduce them:
     // per k-block the maximum of the non-NaN bytes over each 16 rows (DPP), and per 64 rows
     // (a wave) whether a NaN byte occurs.
     {
-        const uint32_t row = tid & 255u, part = tid >> 8;
+        const uint32_t row = tid;
         uint32_t v[2] = {0u, 0u};
         if (row < n_rows) {
             const uint8_t *p = a.sf_row + (size_t)(row_base + m0 + row) * Kb + k0 / 32u;
-            if (PARTS == 1) {
-                if (cols > 128u) { // one request at any 4-byte alignment
-                    const u32x2 t = *reinterpret_cast<const u32x2_unaligned *>(p);
-                    v[0] = t.x;
-                    v[1] = t.y;
-                } else {
-                    v[0] = reinterpret_cast<const uint32_t *>(p)[0];
-                }
-            } else if (part == 0u || cols > 128u) {
-                v[0] = reinterpret_cast<const uint32_t *>(p)[part];
+            if (cols > 128u) { // one request at any 4-byte alignment
+                const u32x2 t = *reinterpret_cast<const u32x2_unaligned *>(p);
+                v[0] = t.x;
+                v[1] = t.y;
+            } else {
+                v[0] = reinterpret_cast<const uint32_t *>(p)[0];
             }
         }
         uint32_t mx[2] = {0u, 0u}, nan_bits = 0;
 #pragma unroll
-        for (int j = 0; j < KBT; ++j) {
+        for (int j = 0; j < 8; ++j) {
             const uint32_t b = (v[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-            s_row_sf[(part * KBT + j) * TILE_M + row] = (uint8_t)b;
+            s_row_sf[j * TILE_M + row] = (uint8_t)b;
             nan_bits |= (__ballot(b == 255u) != 0ull ? 1u : 0u) << j;
             uint32_t t = b == 255u ? 0u : b;
             t = max(t, dpp_read<DPP_QUAD_XOR1>(t));
@@ -213,13 +179,13 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
         }
         if ((tid & 15u) == 0u) {
 #pragma unroll
-            for (int j = 0; j < KBT; ++j)
-                s_max16[(part * KBT + j) * 16 + (row >> 4)] = (uint8_t)(mx[j >> 2] >> (8 * (j & 3)));
+            for (int j = 0; j < 8; ++j)
+                s_max16[j * 16 + (row >> 4)] = (uint8_t)(mx[j >> 2] >> (8 * (j & 3)));
         }
         if ((tid & 63u) == 0u) {
 #pragma unroll
-            for (int j = 0; j < KBT; ++j)
-                s_nan[(row >> 6) * 8 + part * KBT + j] = (uint8_t)((nan_bits >> j) & 1u);
+            for (int j = 0; j < 8; ++j)
+                s_nan[(row >> 6) * 8 + j] = (uint8_t)((nan_bits >> j) & 1u);
         }
     }
     if (staged) {
@@ -288,11 +254,10 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
     for (int h = 0; h < SPL; ++h)
         slot[h] = (rgl * SPL + h + cg) & 15u;
 
-    static_for<PHASES>([&](auto php) {
-        constexpr int ph = decltype(php)::value;
+    {
         if (active) {
-            static_for<CP / 2>([&](auto jjp) {
-                constexpr int j = ph * (CP / 2) + decltype(jjp)::value; // nibble byte: columns 2j, 2j+1
+            static_for<4>([&](auto jjp) {
+                constexpr int j = decltype(jjp)::value; // nibble byte: columns 2j, 2j+1
                 uint32_t o[2][RPL / 4];
                 static_for<RPL / 4>([&](auto rp) {
                     constexpr int r = decltype(rp)::value; // rows 4r..4r+3 -> dword r of both columns
@@ -311,7 +276,7 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
                 });
 #pragma unroll
                 for (int cc = 0; cc < 2; ++cc) {
-                    const uint32_t row = ((2 * j + cc) - ph * CP) * 32u + cg; // LDS k-row of column 2j+cc
+                    const uint32_t row = (2 * j + cc) * 32u + cg; // LDS k-row of column 2j+cc
 #pragma unroll
                     for (int h = 0; h < SPL; ++h)
                         s_out[row * 16u + slot[h]] =
@@ -328,18 +293,15 @@ __global__ void __launch_bounds__(T_THREADS, MXFP4_F8C_WAVES) row_to_fp8_col_ker
                         continue;
                     const uint32_t sl = (rgl * SPL + (i >> 4) + cg) & 15u;
 #pragma nounroll
-                    for (uint32_t c = 0; c < (uint32_t)CP; ++c)
+                    for (uint32_t c = 0; c < 8u; ++c)
                         bytes[((c * 32u + cg) * 16u + sl) * 16u + (i & 15u)] = 0x7Fu;
                 }
             }
         }
         __syncthreads();
 
-        write_part_out<CP, T_THREADS, MXFP4_F8C_NT != 0>(s_out, out_x + (size_t)(k0 + ph * CP) * pitch_x + m0, out_x,
-                                                         pitch_x, cols, n_rows, tid);
-        if (ph + 1 < PHASES)
-            __syncthreads(); // the LDS part is free again
-    });
+        write_tile_out(s_out, out_x + (size_t)k0 * pitch_x + m0, out_x, pitch_x, cols, n_rows, tid);
+    }
 }
 
 hipError_t launch_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
@@ -359,7 +321,7 @@ hipError_t launch_row_to_fp8_col(const uint8_t *q_row, const uint8_t *sf_row, co
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    a.stage_in = total >= 8u * 256u && MXFP4_F8C_STAGE_IN ? 1u : 0u;
+    a.stage_in = total >= 8u * 256u ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();

@@ -24,10 +24,6 @@
 #include "mxfp4_device.hpp"
 #include "mxfp4_kernels.hpp"
 
-#ifndef MXFP4_F8CR_STAGE_IN
-#define MXFP4_F8CR_STAGE_IN 1
-#endif
-
 namespace mxfp4 {
 
 namespace fp8col_requant {
@@ -383,7 +379,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
     }
     __syncthreads();
 
-    write_part_out<8, T_THREADS, true>(s_out, out_x + (size_t)k0 * pitch_x + m0, out_x, pitch_x, cols, n_rows, tid);
+    write_tile_out(s_out, out_x + (size_t)k0 * pitch_x + m0, out_x, pitch_x, cols, n_rows, tid);
 }
 
 hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf_row, const int32_t *expert_offsets,
@@ -403,7 +399,7 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    a.stage_in = total >= 8u * 256u && MXFP4_F8CR_STAGE_IN ? 1u : 0u;
+    a.stage_in = total >= 8u * 256u ? 1u : 0u;
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_requant_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
