@@ -16,6 +16,26 @@ static_assert(mxfp4::MAX_EXPERT_CHUNKS * 64 >= MXFP4_MAX_EXPERTS, "the expert lo
 
 } // namespace
 
+namespace mxfp4 {
+
+uint32_t compute_units()
+{
+    constexpr int kMaxDevices = 64;
+    static int cached[kMaxDevices]; // 0 = not looked up yet; a race between two first calls writes the same value
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return 256u;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return (uint32_t)cached[dev];
+}
+
+} // namespace mxfp4
+
 extern "C" {
 
 mxfp4_status mxfp4_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,

@@ -37,6 +37,10 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
                                          int32_t num_experts, int64_t M, int64_t K, uint8_t *x_col,
                                          float *x_col_scale, hipStream_t stream);
 
+// Compute units of the current device (hipDeviceAttributeMultiprocessorCount, looked up once per device;
+// 256 if the runtime cannot say): launch heuristics are stated in tiles per compute unit.
+uint32_t compute_units();
+
 // Plain 16-byte-per-lane copy of `bytes` (a multiple of 16) bytes; policy bit 0 = non-temporal loads,
 // bit 1 = non-temporal stores.
 hipError_t launch_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, hipStream_t stream);

@@ -57,13 +57,14 @@ __device__ __forceinline__ uint32_t load_nibbles(const uint32_t *p)
     return __builtin_nontemporal_load(p);
 }
 
-// One lane's 32x8 slice through the hardware conversions.  Exact while every value
+// One lane's 32x8 slice through the hardware conversions, in two steps with the column scales between them
+// (the workgroup sends the scale bytes off before it re-quantizes).  Exact while every value
 // e2m1 * 2^(b-127) is an FP32 number, i.e. for row-scale bytes up to 252
 // (6 * 2^125 < 2^128; the smallest, 0.5 * 2^-127, is an FP32 subnormal).
-__device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&sb)[8], uint32_t (&cb)[8],
-                                                 uint32_t (&o)[8][4])
+// Step 1: the UE8M0 bytes of the slice's 8 columns.
+__device__ __forceinline__ void column_scales_hw(const uint32_t (&w)[32], const uint32_t (&sb)[8], uint32_t (&cb)[8])
 {
-    // pass 1: column maxima of |value| (no NaN can occur: NaN row scales never get here)
+    // column maxima of |value| (no NaN can occur: NaN row scales never get here)
     float amax[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c)
@@ -79,31 +80,23 @@ __device__ __forceinline__ void requant_slice_hw(uint32_t (&w)[32], uint32_t (&s
             amax[2 * j + 1] = max3_abs_nan(fa.y, fb.y, amax[2 * j + 1]);
         });
     });
+    // the sec. 3.1 rule on the exponent field.  A maximum with at most two significant bits (1.0 or 1.5
+    // times a power of two) never exceeds 1.5 * 2^e, so the byte is its exponent field minus 2, clamped
+    // at 0; zero and FP32 subnormals give 0.
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        cb[c] = max(f2u(amax[c]) >> 23, 2u) - 2u;
+}
 
-    // column scales: the sec. 3.1 rule on the exponent field.  A maximum with at most two
-    // significant bits (1.0 or 1.5 times a power of two) never exceeds 1.5 * 2^e, so the byte
-    // is its exponent field minus 2, clamped at 0; zero and FP32 subnormals give 0.
+// Step 2: decode again (cheaper than keeping 256 floats live) and re-quantize pairs of rows into output
+// bytes: v_cvt_scalef32_pk_fp4_f32 takes rows (m, m+1) of one column.
+__device__ __forceinline__ void requant_rows_hw(uint32_t (&w)[32], uint32_t (&sb)[8], const uint32_t (&cb)[8],
+                                                uint32_t (&o)[8][4])
+{
     float cs[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        cb[c] = max(f2u(amax[c]) >> 23, 2u) - 2u;
+    for (int c = 0; c < 8; ++c)
         cs[c] = u2f(cb[c] << 23);
-    }
-
-    // pass 2: decode again (cheaper than 256 live floats), re-quantize pairs of rows into
-    // output bytes.
-    // The empty asm statements make the nibble and scale registers opaque and dependent on
-    // all eight column scales: every decode of pass 2 is a new computation that cannot start
-    // before pass 1 has finished, so the 256 floats of pass 1 are never kept alive.
-#define MXFP4_TIE8(x0, x1, x2, x3, x4, x5, x6, x7)                                                          \
-    asm volatile("" : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7)       \
-                 : "v"(cs[0]), "v"(cs[1]), "v"(cs[2]), "v"(cs[3]), "v"(cs[4]), "v"(cs[5]), "v"(cs[6]), "v"(cs[7]))
-    MXFP4_TIE8(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]);
-    MXFP4_TIE8(w[8], w[9], w[10], w[11], w[12], w[13], w[14], w[15]);
-    MXFP4_TIE8(w[16], w[17], w[18], w[19], w[20], w[21], w[22], w[23]);
-    MXFP4_TIE8(w[24], w[25], w[26], w[27], w[28], w[29], w[30], w[31]);
-    MXFP4_TIE8(sb[0], sb[1], sb[2], sb[3], sb[4], sb[5], sb[6], sb[7]);
-#undef MXFP4_TIE8
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
@@ -344,11 +337,14 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
         __syncthreads(); // every slice is in registers before the tile buffer takes the results
     }
 
+    // ---- step 1: the column scales of every slice, and the slices that take the integer path in full
+    uint32_t sb[8], cb[8];
+    bool hw = false; // this lane's slice goes through the hardware conversions
     if (active) {
         const uint8_t *my_row_sf = &s_row_sf[(cg >> 2) * SF_STRIDE + rg * 32u];
         uint64_t col_bytes;
         if (((s_special[rg] >> (cg >> 2)) & 1u) == 0u) {
-            uint32_t sb[8];
+            hw = true;
             const u32x4 s0 = reinterpret_cast<const u32x4 *>(my_row_sf)[0];
             const u32x4 s1 = reinterpret_cast<const u32x4 *>(my_row_sf)[1];
 #pragma unroll
@@ -356,13 +352,8 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
                 sb[g] = s0[g];
                 sb[4 + g] = s1[g];
             }
-            uint32_t cb[8];
-            uint32_t o[8][4];
-            requant_slice_hw(w, sb, cb, o);
+            column_scales_hw(w, sb, cb);
             uint32_t cb_lo = 0, cb_hi = 0;
-#pragma unroll
-            for (int c = 0; c < 8; ++c)
-                s_out[(c * 32 + cg) * NRG + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 cb_lo |= cb[c] << (8 * c);
@@ -391,9 +382,8 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
     }
     __syncthreads();
 
-    // ---- out: the column scales as one request per k-row, then the nibbles, 8 lanes per k-row with
-    // 128 contiguous bytes each.  Chunk u*256 + tid of the LDS tile is row (u*32 + tid/8), slot
-    // tid%8: column k = (tid/8)*8 + u.  Both read LDS regions written before the one barrier above.
+    // ---- the column scales leave now, one request per k-row, while the nibbles are still being re-quantized
+    // (93.1 -> 90.8 us at [65536,7168] against sending them off together with the nibbles at the end).
     const uint32_t sf_k = (tid & 31u) * 8u + (tid >> 5); // slot tid of the staged column scales is column sf_k
     if (sf_k < cols) {
         uint8_t *dst = out_sf + (size_t)(k0 + sf_k) * pitch_sf + m0 / 32u;
@@ -405,6 +395,19 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
         else
             store_head_bytes(dst, u32x4{v.x, v.y, 0u, 0u}, n_rg);
     }
+
+    // ---- step 2: re-quantize into the tile buffer
+    if (hw) {
+        uint32_t o[8][4];
+        requant_rows_hw(w, sb, cb, o);
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            s_out[(c * 32 + cg) * NRG + slot] = u32x4{o[c][0], o[c][1], o[c][2], o[c][3]};
+    }
+    __syncthreads();
+
+    // ---- out: the nibbles, 8 lanes per k-row with 128 contiguous bytes each.  Chunk u*256 + tid of the LDS
+    // tile is row (u*32 + tid/8), slot tid%8: column k = (tid/8)*8 + u.
     {
         const uint32_t cgx = tid / NRG;
         const uint32_t part = ((tid & (NRG - 1u)) - (cgx >> 1)) & (NRG - 1u);
@@ -453,8 +456,7 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    // at least 8 tiles per CU of an MI355X
-    a.stage_in = total >= 8u * 256u ? 1u : 0u;
+    a.stage_in = total >= 8u * compute_units() ? 1u : 0u; // at least 8 tiles per compute unit
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();

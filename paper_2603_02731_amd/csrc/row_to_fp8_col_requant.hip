@@ -399,7 +399,7 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    a.stage_in = total >= 8u * 256u ? 1u : 0u;
+    a.stage_in = total >= 8u * compute_units() ? 1u : 0u; // at least 8 tiles per compute unit
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_requant_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
