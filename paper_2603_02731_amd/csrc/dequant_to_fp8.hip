@@ -80,6 +80,64 @@ static_assert(make_underflow_table().lo[0] == 0x0c080400u && make_underflow_tabl
               "d = 12 row");
 static_assert(make_underflow_table().lo[7] == 0 && make_underflow_table().hi[7] == 0, "d = 19 row is zero");
 
+// One half-block: 16 packed nibbles (two dwords) and their block's scale byte -> 16 E4M3 bytes.  The 8 lanes of
+// a 128-element tile call it together (lanes 2j, 2j+1 hold block j) and agree on the tile maximum by DPP.
+// Returns the tile's maximum non-NaN scale byte and whether any of its four bytes is NaN.
+__device__ __forceinline__ u32x4 dequant_half_block(const u32x2 w, const uint32_t b, uint32_t *tile_max, uint32_t *tile_nan)
+{
+    // max over the tile's non-NaN scale bytes, and whether any of them is NaN.  Mirroring the 8 lanes pairs
+    // block j with block 3-j, swapping quad halves pairs the two results.
+    const uint32_t is_nan = b == 255u ? 1u : 0u;
+    uint32_t bmax = is_nan ? 0u : b;
+    uint32_t any_nan = is_nan;
+    bmax = max(bmax, dpp_read<DPP_ROW_HALF_MIRROR>(bmax));
+    any_nan |= dpp_read<DPP_ROW_HALF_MIRROR>(any_nan);
+    bmax = max(bmax, dpp_read<DPP_QUAD_XOR2>(bmax));
+    any_nan |= dpp_read<DPP_QUAD_XOR2>(any_nan);
+
+    // the block's 8-entry table: magnitude code -> E4M3 magnitude byte
+    const uint32_t d = bmax - (is_nan ? bmax : b);
+    uint32_t t_lo, t_hi;
+    if (d <= 11u) {
+        t_lo = 0x6c686000u - d * 0x08080800u; // 0, 2^5, 2^6, 1.5*2^6 in E4M3, minus d binades
+        t_hi = 0x7c787470u - d * 0x08080808u; // 2^7, 1.5*2^7, 2^8, 1.5*2^8
+    } else {
+        const uint32_t i = min(d - 12u, 7u);
+        t_lo = c_underflow.lo[i];
+        t_hi = c_underflow.hi[i];
+    }
+    uint32_t sign_even = 0x08080808u, sign_odd = 0x80808080u;
+    if (is_nan) { // a NaN scale byte: the block's 32 outputs are the E4M3 NaN 0x7F
+        t_lo = t_hi = 0x7f7f7f7fu;
+        sign_even = sign_odd = 0u;
+    }
+
+    u32x4 o;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint32_t wj = w[j];
+        const uint32_t mag_even = perm(t_hi, t_lo, wj & 0x07070707u);
+        const uint32_t mag_odd = perm(t_hi, t_lo, (wj >> 4) & 0x07070707u);
+        const uint32_t even = mag_even | ((wj & sign_even) << 4);
+        const uint32_t odd = mag_odd | (wj & sign_odd);
+        o[2 * j] = perm(odd, even, 0x05010400u);     // elements 0..3 of this dword
+        o[2 * j + 1] = perm(odd, even, 0x07030602u); // elements 4..7
+    }
+    *tile_max = bmax;
+    *tile_nan = any_nan;
+    return o;
+}
+
+// FP32 tile scale 2^(bmax - 6 - 127): the byte goes straight into the FP32 exponent field; below exponent
+// field 1 the same power of two is an FP32 subnormal.
+__device__ __forceinline__ float tile_scale_of(uint32_t bmax, uint32_t any_nan)
+{
+    const int b8 = (int)bmax - 6;
+    uint32_t bits = b8 >= 1 ? (uint32_t)b8 << 23 : 0x00400000u >> (uint32_t)(-b8);
+    bits = any_nan ? 0x7fc00000u : bits;
+    return u2f(bits);
+}
+
 struct DequantArgs {
     const uint8_t *q;
     const uint8_t *sf;
@@ -126,60 +184,19 @@ __global__ void __launch_bounds__(DEQUANT_THREADS) dequant_to_fp8_kernel(const D
         const uint32_t c = c0 + u * DEQUANT_THREADS;
         if (c >= a.n_halves)
             break;
-        const uint32_t b = sfb[u];
-
-        // max over the tile's non-NaN scale bytes, and whether any of them is NaN.  Lanes
-        // 2j, 2j+1 of the tile's 8 hold block j: mirroring the 8 pairs block j with block 3-j,
-        // swapping quad halves pairs the two results.
-        const uint32_t is_nan = b == 255u ? 1u : 0u;
-        uint32_t bmax = is_nan ? 0u : b;
-        uint32_t any_nan = is_nan;
-        bmax = max(bmax, dpp_read<DPP_ROW_HALF_MIRROR>(bmax));
-        any_nan |= dpp_read<DPP_ROW_HALF_MIRROR>(any_nan);
-        bmax = max(bmax, dpp_read<DPP_QUAD_XOR2>(bmax));
-        any_nan |= dpp_read<DPP_QUAD_XOR2>(any_nan);
-
-        // the block's 8-entry table: magnitude code -> E4M3 magnitude byte
-        const uint32_t d = bmax - (is_nan ? bmax : b);
-        uint32_t t_lo, t_hi;
-        if (d <= 11u) {
-            t_lo = 0x6c686000u - d * 0x08080800u; // 0, 2^5, 2^6, 1.5*2^6 in E4M3, minus d binades
-            t_hi = 0x7c787470u - d * 0x08080808u; // 2^7, 1.5*2^7, 2^8, 1.5*2^8
-        } else {
-            const uint32_t i = min(d - 12u, 7u);
-            t_lo = c_underflow.lo[i];
-            t_hi = c_underflow.hi[i];
-        }
-        uint32_t sign_even = 0x08080808u, sign_odd = 0x80808080u;
-        if (is_nan) { // a NaN scale byte: the block's 32 outputs are the E4M3 NaN 0x7F
-            t_lo = t_hi = 0x7f7f7f7fu;
-            sign_even = sign_odd = 0u;
-        }
-
-        u32x4 o;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t wj = w[u][j];
-            const uint32_t mag_even = perm(t_hi, t_lo, wj & 0x07070707u);
-            const uint32_t mag_odd = perm(t_hi, t_lo, (wj >> 4) & 0x07070707u);
-            const uint32_t even = mag_even | ((wj & sign_even) << 4);
-            const uint32_t odd = mag_odd | (wj & sign_odd);
-            o[2 * j] = perm(odd, even, 0x05010400u);     // elements 0..3 of this dword
-            o[2 * j + 1] = perm(odd, even, 0x07030602u); // elements 4..7
-        }
+        uint32_t bmax, any_nan;
+        const u32x4 o = dequant_half_block(w[u], sfb[u], &bmax, &any_nan);
         store_streaming(a.x + (size_t)c * 16, o);
 
-        if ((threadIdx.x & 7u) == 0u) {
-            // 2^(bmax - 6 - 127): the byte goes straight into the FP32 exponent field; below
-            // exponent field 1 the same power of two is an FP32 subnormal.
-            const int b8 = (int)bmax - 6;
-            uint32_t bits = b8 >= 1 ? (uint32_t)b8 << 23 : 0x00400000u >> (uint32_t)(-b8);
-            bits = any_nan ? 0x7fc00000u : bits;
-            a.x_scale[c >> 3] = u2f(bits);
-        }
+        if ((threadIdx.x & 7u) == 0u)
+            a.x_scale[c >> 3] = tile_scale_of(bmax, any_nan);
     }
 }
 
+// Row-strided inputs (per-token records of nibbles then scale bytes) go through the same kernel with the row
+// index divided out per lane.  Measured and not built: a workgroup fetching 1, 2, 4 or 8 whole rows with 16-byte
+// loads into LDS and converting from there (262144 records of 3808 bytes: 500-644 us against 488 us) -- the
+// load / barrier / convert phases of such a workgroup overlap worse than this kernel's independent lanes.
 hipError_t launch_dequant_to_fp8(const uint8_t *q, int64_t ld_q, const uint8_t *sf, int64_t ld_sf,
                                  int64_t M, int64_t K, uint8_t *x, float *x_scale, hipStream_t stream)
 {

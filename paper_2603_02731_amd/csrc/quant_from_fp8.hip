@@ -226,8 +226,8 @@ __global__ void __launch_bounds__(QUANT_THREADS_ROUTED) quant_from_fp8_scatter_k
 // as scattered dwords.
 // The destination indices of a row are uniform over the workgroup.
 constexpr int SCATTER_ROWS = 4; // at most; the launcher picks 1, 2 or 4 rows per workgroup
-constexpr int SCATTER_THREADS = 256;
-constexpr int SCATTER_UNROLL = 4;
+constexpr int SCATTER_THREADS = 512;
+constexpr int SCATTER_UNROLL = 1;
 
 template <bool WIDE_SF> // the K/32 scale bytes of a row are a whole number of 16-byte pieces (K % 512 == 0)
 __global__ void __launch_bounds__(SCATTER_THREADS) quant_from_fp8_scatter_rows_kernel(const QuantScatterArgs a,
@@ -339,13 +339,16 @@ hipError_t launch_quant_from_fp8_scatter(const uint8_t *x, const float *x_scale,
     const bool rows16 = ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(sf) | (uintptr_t)ld_q |
                           (uintptr_t)ld_sf) & 15u) == 0u;
     if (rows16 && rec <= 48u * 1024u) {
-        // rows per workgroup: about two chunks per lane.  Top-8 payload of 65536 tokens at K = 7168 into records,
-        // over rotated buffers: 1 row 558 us, 2 rows 570, 4 rows 588, 8 rows 597 (more, shorter workgroups
-        // overlap their loads, stores and the wait for the last store better); the kernel it replaces, with
-        // 8-byte nibble stores and the scale dwords on their own, 598 us.  A kernel that only copies 16 bytes per
-        // lane to eight destination streams needs 395-430 us for the same bytes.
+        // Rows per workgroup: about one 16-element chunk per lane.  Top-8 payload of 65536 tokens at K = 7168 into
+        // 3808-byte records, over rotated buffers, destinations shuffled / in token order: 512 lanes x 1 chunk, one
+        // row 552 / 427 us; 256 lanes x 4 chunks, one row 545 / 458, four rows 588 / 545; two rows on 896 lanes
+        // 597 / 559 (more, shorter workgroups overlap their loads, stores and the wait for the last store better).
+        // The kernel it replaces, with 8-byte nibble stores and the scale dwords on their own: 598 us shuffled.
+        // With shuffled destinations the records bound it: 3808 bytes are 29.75 lines, so both ends of every
+        // record are partial lines written by different workgroups (planes of 3584 + 224 bytes: 516 us; a kernel
+        // that only copies 16 bytes per lane to eight destination streams: 395-430 us).
         const uint32_t C = a.chunks_per_row;
-        const uint32_t rows = C >= SCATTER_THREADS ? 1u : C >= SCATTER_THREADS / 2u ? 2u : 4u;
+        const uint32_t rows = 2u * C >= SCATTER_THREADS ? 1u : 4u * C >= SCATTER_THREADS ? 2u : 4u;
         const uint32_t blocks = (uint32_t)((M_src + rows - 1) / rows);
         if (K % 512 == 0)
             hipLaunchKernelGGL(quant_from_fp8_scatter_rows_kernel<true>, dim3(blocks), dim3(SCATTER_THREADS),
