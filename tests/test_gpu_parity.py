@@ -539,6 +539,39 @@ def test_quant_scatter_equals_gather_and_leaves_other_rows_alone():
     assert_same(got[one[:, 0], K // 2:], fsf, "scatter into records: scale bytes")
 
 
+@pytest.mark.parametrize("K,M,fan,pad", [(512, 37, 8, 0), (7168, 133, 8, 0), (7168, 64, 11, 32), (640, 203, 3, 12),
+                                          (1536, 50, 1, 0), (16384, 9, 2, 0), (32768, 5, 9, 0), (2048, 130, 8, 16)])
+def test_quant_scatter_whole_rows_through_lds(K, M, fan, pad):
+    """Outputs whose rows start on 16-byte boundaries take the kernel that writes whole rows out of LDS: records
+    of K/2 + K/32 bytes (plus padding), 1, 2 or 4 rows per workgroup, scale bytes as 16-byte pieces (K % 512 == 0)
+    or dwords, fan-outs beyond the eight prefetched indices, row counts that end inside a workgroup, entries that
+    point nowhere; the bytes between and around the records stay as they were."""
+    rng = np.random.default_rng(K + M)
+    x8, s = synth.student_t_fp8(M, K, seed=K % 97)
+    x8, s = x8.numpy(), s.numpy()
+    x8[rng.integers(0, M), rng.integers(0, K)] = 0x7F                   # a NaN block
+    x8[rng.integers(0, M)] = 0                                          # a zero row
+    M_out = M * fan + 7
+    dst = rng.permutation(M_out)[:M * fan].reshape(M, fan).astype(np.int32)
+    nowhere = rng.random(dst.shape) < 0.05
+    dst[nowhere] = rng.choice(np.array([-1, -7, M_out, 2 ** 31 - 1], np.int32), size=int(nowhere.sum()))
+    rec = (K // 2 + K // 32 + 15) // 16 * 16 + pad // 16 * 16
+    assert rec % 16 == 0
+    guard = 256
+    buf = torch.full((guard + M_out * rec + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    recs = buf[guard:guard + M_out * rec]
+    assert recs.data_ptr() % 16 == 0
+    mx.mxfp4_quant_from_fp8_scatter(dev(x8), dev(s), dev(dst), M_out, q=recs, sf=recs[K // 2:], ld_q=rec, ld_sf=rec)
+    got = host(buf)
+    assert (got[:guard] == 0xA5).all() and (got[guard + M_out * rec:] == 0xA5).all(), "written outside the records"
+    got = got[guard:guard + M_out * rec].reshape(M_out, rec)
+    wq, wsf = ref.quant_from_fp8_scatter(x8, s, dst, M_out, q=np.full((M_out, K // 2), 0xA5, np.uint8),
+                                         sf=np.full((M_out, K // 32), 0xA5, np.uint8))
+    assert_same(got[:, K // 2:K // 2 + K // 32], wsf, "scatter through LDS: scale bytes")
+    assert_same(got[:, :K // 2], wq, "scatter through LDS: nibbles")
+    assert (got[:, K // 2 + K // 32:] == 0xA5).all(), "padding of the records written"
+
+
 # ------------------------------------------------------------------ streams and graphs
 
 def test_side_stream_and_graph_replays():
