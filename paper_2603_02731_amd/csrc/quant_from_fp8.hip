@@ -81,7 +81,7 @@ __device__ __forceinline__ void quant16(const u32x4 w, float s, uint32_t out[2],
     *scale_byte = b;
 }
 
-// store_streaming instead of the non-temporal hint, measured at [65536,7168]: the 8-byte nibble stores of the
+// store_streaming instead of the non-temporal hint, measured at [65536,7168] on one buffer set: the 8-byte nibble stores of the
 // dense kernel 112.0 -> 112.1 us (no difference), its scale dwords 112 -> 121 us, the scattered rows
 // 463 -> 466 us, gathered per-token records 1065 -> 1400 us: not used here.
 //
