@@ -19,6 +19,7 @@ step would run them, are reported beside it ("in_step"), labelled as such.
   kernels.*.in_step    one buffer set, HIP events around each kernel in every N-th step
   roofline             the kernel with the LOWEST cold fraction of the 8 TB/s HBM peak
   copy                 the library's own 16-byte-per-lane copy over the same rotated sets
+  movers               the bytes of each kernel moved in its read : write mix and access pattern, no arithmetic
   configs              the smaller named workloads ([4096,7168], [16384,2048], 32 ragged experts,
                        the top-8 dispatch payload), cold and on a single set
   cpu_baseline         the CPU oracle on the host cores, on a bounded sample of the workload
@@ -342,9 +343,30 @@ def main():
         best = max(pol.values())
         out["copy"] = {"GB/s": best, "frac_of_hbm_peak": best / HBM_PEAK_GBPS, "by_policy_GB/s": pol,
                        "what": "mxfp4_stream_copy, 16-byte loads and stores, rotated sets"}
+        # the same bytes as each kernel moves (without its scales), in its read : write mix and access pattern,
+        # by kernels that do no arithmetic: what this GPU gives the pattern itself
+        movers = {
+            "quant": ("mxfp4_stream_mix 2:1 (16 B read, 8 B written per lane)", 1.5 * n,
+                      lambda t: mx.mxfp4_stream_mix(t["x8"].view(-1), t["q"].view(-1), 1)),
+            "dequant": ("mxfp4_stream_mix 1:2 (8 B read, 16 B written per lane)", 1.5 * n,
+                        lambda t: mx.mxfp4_stream_mix(t["q"].view(-1), t["xb"].view(-1), 2)),
+            "row_to_col": ("mxfp4_tile_copy (256 x 128-byte tiles read, 256 pieces of 128 B written each)", 1.0 * n,
+                           lambda t: mx.mxfp4_tile_copy(t["q"], t["xb"].view(-1))),
+            "read_only": ("mxfp4_stream_mix read only", 1.0 * n,
+                          lambda t: mx.mxfp4_stream_mix(t["x8"].view(-1), t["sb"].view(torch.uint8).view(-1), 3)),
+        }
+        out["movers"] = {}
+        for k, (what, nbytes, fn) in movers.items():
+            us = B.timed([lambda t=t, fn=fn: fn(t) for t in S], 30)
+            out["movers"][k] = {"what": what, "us": us, "bytes": nbytes, "GB/s": nbytes / us * 1e-3,
+                                "frac_of_hbm_peak": nbytes / us * 1e-3 / HBM_PEAK_GBPS}
         for k in names:
             if "cold" in kernels[k]:
                 kernels[k]["cold"]["frac_of_measured_copy"] = kernels[k]["cold"]["GB/s"] / best
+                kernels[k]["cold"]["frac_of_its_mover"] = kernels[k]["cold"]["GB/s"] / out["movers"][k]["GB/s"]
+        for t in S:  # the movers wrote over the MXFP4 and FP8 outputs: every set holds valid data again
+            quant(t), dequant(t), row_to_col(t)
+        torch.cuda.synchronize()
 
     if "configs" in phases:
         out["configs"] = time_configs(B, S[0])
@@ -476,7 +498,15 @@ def time_configs(B, target):
         res["config5_quant_gather_top8_records"] = B.cold_and_single(
             [lambda b=b: mx.mxfp4_quant_from_fp8(x8, s, gather_idx=idx, q=b, sf=b[K // 2:], ld_q=rec, ld_sf=rec)
              for b in bufs], nbq, 5, rows_out=Mo, bytes_are="compulsory: source once + indices + payload")
-        del bufs
+        # the write traffic of the scatter without the quantizer: 65536 ready records, each written to the same 8
+        # destinations (a mover: it reads half the bytes of the quantizer and does no arithmetic)
+        recs = torch.randint(0, 256, (M, rec), dtype=torch.uint8, device=dev)
+        res["config5_record_fanout_mover"] = B.cold_and_single(
+            [lambda b=b: mx.mxfp4_record_fanout(recs, dst, b) for b in bufs], M * rec + Mo * 4 + Mo * rec, 10,
+            rows_out=Mo, bytes_are="the mover's own: records once + indices + payload")
+        res["config5_quant_scatter_top8_records"]["cold"]["time_of_its_mover_over_its_time"] = (
+            res["config5_record_fanout_mover"]["cold"]["us"] / res["config5_quant_scatter_top8_records"]["cold"]["us"])
+        del bufs, recs
     return res
 
 

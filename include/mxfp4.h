@@ -187,13 +187,37 @@ mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const ui
                                                   int64_t M_total, int64_t K, uint8_t *x_col,
                                                   float *x_col_scale, void *hip_stream);
 
-/* Measurement aid, not a conversion: a plain copy of `bytes` bytes with one 16-byte load and one 16-byte
- * store per lane, the access width of the conversion kernels.  The conversions are bandwidth-bound (the
- * paper places their cost in global-memory traffic, sec. 3.4 and 4.3), so their rates are reported beside
- * what this copy reaches on the same GPU in the same run.
- *   src, dst  device pointers, 16-byte aligned, not overlapping;  bytes a multiple of 16
- *   policy    bit 0: non-temporal loads, bit 1: non-temporal stores (0..3) */
+/* Measurement aids, not conversions: byte movers without arithmetic.  The conversions are bandwidth-bound (the
+ * paper places their cost in global-memory traffic, sec. 3.4 and 4.3), so their rates are reported beside what
+ * a kernel reaches on the same GPU, in the same run, that only moves their bytes.
+ *
+ * mxfp4_stream_mix: `bytes` (a multiple of 16) bytes of the WIDER side, one 16-byte access per lane.
+ *   mix 0  1:1 copy: src and dst of `bytes` bytes
+ *   mix 1  2:1, the quantizer's mix: `bytes` read, bytes/2 written
+ *   mix 2  1:2, the de-quantizer's mix: bytes/2 read, `bytes` written
+ *   mix 3  read only: `bytes` read (dst must still be a valid pointer; one byte of it may be written)
+ *   policy bit 0: non-temporal loads, bit 1: non-temporal stores (0..3)
+ *   src, dst  device pointers, 16-byte aligned, not overlapping
+ * mxfp4_stream_copy(src, dst, bytes, policy) is mix 0.
+ *
+ * mxfp4_tile_copy: the access pattern of the row->column conversions without the conversion.  src is a
+ * row-major byte matrix [rows, row_bytes] (rows % 256 == 0, row_bytes % 128 == 0), dst the [2 * row_bytes,
+ * rows / 2] byte matrix of the transposed nibble layout; every 256 x 128-byte tile of src is read with
+ * 16-byte loads and written as 256 pieces of 128 bytes, piece i to row 256 * (tile column) + i of dst at
+ * byte 128 * (tile row), in the tile order of the conversions.  The bytes inside a piece are not rearranged
+ * (dst is not a transposition of src): it moves the nibble bytes mxfp4_row_to_col moves, where it moves them. */
 mxfp4_status mxfp4_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, void *hip_stream);
+mxfp4_status mxfp4_stream_mix(const void *src, void *dst, int64_t bytes, int32_t policy, int32_t mix,
+                              void *hip_stream);
+mxfp4_status mxfp4_tile_copy(const void *src, void *dst, int64_t rows, int64_t row_bytes, void *hip_stream);
+
+/* Measurement aid: the write traffic of mxfp4_quant_from_fp8_scatter without the quantizer.  Record i of src
+ * (rec_bytes bytes at src + i * ld_src; rec_bytes a multiple of 16 up to 48 KiB, ld_src a multiple of 16) is
+ * read once and written to the records dst_idx[i * fanout + j], j < fanout, of dst (record d at
+ * dst + d * rec_bytes); entries outside [0, M_out) are skipped.  src, dst 16-byte aligned device pointers,
+ * dst_idx int32 [M_src, fanout] on the device. */
+mxfp4_status mxfp4_record_fanout(const void *src, int64_t ld_src, const int32_t *dst_idx, int64_t M_src,
+                                 int32_t fanout, int64_t rec_bytes, int64_t M_out, void *dst, void *hip_stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *mxfp4_status_string(mxfp4_status status);

@@ -17,7 +17,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_OFFSETS, ERR_LAUNCH = 0, -1, -2, -3, -4,
 EXPORTS = ("mxfp4_quant_from_fp8", "mxfp4_quant_from_fp8_scatter", "mxfp4_quant_from_bf16", "mxfp4_dequant_to_fp8", "mxfp4_row_to_col",
            "mxfp4_quant_from_fp8_grouped", "mxfp4_row_to_col_grouped", "mxfp4_row_to_fp8_col",
            "mxfp4_row_to_fp8_col_grouped", "mxfp4_row_to_fp8_col_requant", "mxfp4_row_to_fp8_col_requant_grouped",
-           "mxfp4_stream_copy", "mxfp4_status_string")
+           "mxfp4_stream_copy", "mxfp4_stream_mix", "mxfp4_tile_copy", "mxfp4_record_fanout", "mxfp4_status_string")
 
 _lib = None
 _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
@@ -49,6 +49,9 @@ def lib():
         L.mxfp4_row_to_fp8_col_requant.argtypes = L.mxfp4_row_to_fp8_col.argtypes
         L.mxfp4_row_to_fp8_col_requant_grouped.argtypes = L.mxfp4_row_to_fp8_col_grouped.argtypes
         L.mxfp4_stream_copy.argtypes = [_vp, _vp, _i64, _i32, _vp]
+        L.mxfp4_stream_mix.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp]
+        L.mxfp4_tile_copy.argtypes = [_vp, _vp, _i64, _i64, _vp]
+        L.mxfp4_record_fanout.argtypes = [_vp, _i64, _vp, _i64, _i32, _i64, _i64, _vp, _vp]
         for n in EXPORTS[:-1]:
             getattr(L, n).restype = ctypes.c_int
         L.mxfp4_status_string.argtypes = [ctypes.c_int]
@@ -339,11 +342,59 @@ def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_co
 def mxfp4_stream_copy(src, dst, policy=1, stream=None):
     """Plain 16-byte-per-lane copy of src into dst (uint8, same size, a multiple of 16 bytes): the measured
     roof of the conversion kernels.  policy bit 0 = non-temporal loads, bit 1 = non-temporal stores."""
+    return mxfp4_stream_mix(src, dst, 0, policy=policy, stream=stream)
+
+
+def mxfp4_stream_mix(src, dst, mix, policy=3, stream=None):
+    """Byte mover without arithmetic in a read : write mix.  mix 0: copy src -> dst; 1: 2:1 (dst holds half of
+    src's bytes); 2: 1:2 (dst holds twice src's bytes); 3: read src only (dst any non-empty uint8 device tensor)."""
+    mix = int(mix)
+    if mix not in (0, 1, 2, 3):
+        raise ValueError("mix is 0 (1:1), 1 (2:1), 2 (1:2) or 3 (read only)")
     _buf(src, torch.uint8, "src")
-    _buf(dst, torch.uint8, "dst", min_bytes=src.numel())
-    if src.numel() % 16 != 0:
-        raise ValueError("the copy moves whole 16-byte chunks")
+    wide = 2 * src.numel() if mix == 2 else src.numel()
+    if wide % 16 != 0:
+        raise ValueError("the mover works in whole 16-byte chunks")
+    need = {0: wide, 1: wide // 2, 2: wide, 3: 1}[mix]
+    _buf(dst, torch.uint8, "dst", min_bytes=need)
     _on_device(src=src, dst=dst)
-    st = lib().mxfp4_stream_copy(src.data_ptr(), dst.data_ptr(), src.numel(), int(policy), _stream(stream))
-    _check("mxfp4_stream_copy", st)
+    st = lib().mxfp4_stream_mix(src.data_ptr(), dst.data_ptr(), wide, int(policy), mix, _stream(stream))
+    _check("mxfp4_stream_mix", st)
+    return dst
+
+
+def mxfp4_tile_copy(src, dst, stream=None):
+    """src uint8 [rows, row_bytes] moved tile by tile into dst (uint8, at least rows * row_bytes bytes) in the
+    access pattern of mxfp4_row_to_col, without the conversion (rows % 256 == 0, row_bytes % 128 == 0)."""
+    _buf(src, torch.uint8, "src")
+    if src.dim() != 2 or src.shape[0] % 256 != 0 or src.shape[1] % 128 != 0:
+        raise ValueError("src must be [rows % 256 == 0, row_bytes % 128 == 0]")
+    _buf(dst, torch.uint8, "dst", min_bytes=src.numel())
+    _on_device(src=src, dst=dst)
+    st = lib().mxfp4_tile_copy(src.data_ptr(), dst.data_ptr(), src.shape[0], src.shape[1], _stream(stream))
+    _check("mxfp4_tile_copy", st)
+    return dst
+
+
+def mxfp4_record_fanout(src, dst_idx, dst, rec_bytes=None, stream=None):
+    """Record i of src (uint8 [M_src, ld_src]; its first rec_bytes bytes, default the whole row) written to the
+    records dst_idx[i, j] of dst (uint8, a whole number of records of rec_bytes): the write traffic of
+    mxfp4_quant_from_fp8_scatter without the quantizer."""
+    _buf(src, torch.uint8, "src")
+    if src.dim() != 2:
+        raise ValueError("src must be [M_src, ld_src]")
+    M_src, ld = src.shape
+    rec = ld if rec_bytes is None else int(rec_bytes)
+    if rec <= 0 or rec % 16 != 0 or ld % 16 != 0 or rec > ld or rec > 48 * 1024:
+        raise ValueError("records are multiples of 16 bytes up to 48 KiB, no longer than a row of src")
+    _buf(dst_idx, torch.int32, "dst_idx")
+    if dst_idx.dim() != 2 or dst_idx.shape[0] != M_src or dst_idx.shape[1] < 1:
+        raise ValueError("dst_idx must be int32 [M_src, fanout]")
+    _buf(dst, torch.uint8, "dst")
+    if dst.numel() % rec != 0:
+        raise ValueError("dst must hold a whole number of records")
+    _on_device(src=src, dst_idx=dst_idx, dst=dst)
+    st = lib().mxfp4_record_fanout(src.data_ptr(), ld, dst_idx.data_ptr(), M_src, dst_idx.shape[1], rec,
+                                   dst.numel() // rec, dst.data_ptr(), _stream(stream))
+    _check("mxfp4_record_fanout", st)
     return dst

@@ -233,7 +233,13 @@ mxfp4_status mxfp4_row_to_fp8_col_requant_grouped(const uint8_t *q_row, const ui
 
 mxfp4_status mxfp4_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, void *hip_stream)
 {
-    if (bytes < 0 || bytes % 16 != 0 || policy < 0 || policy > 3 || bytes / 16 / 1024 >= ((int64_t)1 << 31))
+    return mxfp4_stream_mix(src, dst, bytes, policy, 0, hip_stream);
+}
+
+mxfp4_status mxfp4_stream_mix(const void *src, void *dst, int64_t bytes, int32_t policy, int32_t mix, void *hip_stream)
+{
+    if (bytes < 0 || bytes % 16 != 0 || policy < 0 || policy > 3 || mix < 0 || mix > 3 ||
+        bytes / 16 / 512 >= ((int64_t)1 << 31))
         return MXFP4_ERR_SHAPE;
     if (bytes == 0)
         return MXFP4_OK;
@@ -241,7 +247,37 @@ mxfp4_status mxfp4_stream_copy(const void *src, void *dst, int64_t bytes, int32_
         return MXFP4_ERR_NULL;
     if (!aligned(src, 16) || !aligned(dst, 16))
         return MXFP4_ERR_ALIGN;
-    return launched(mxfp4::launch_stream_copy(src, dst, bytes, policy, static_cast<hipStream_t>(hip_stream)));
+    return launched(mxfp4::launch_stream_copy(src, dst, bytes / 16, policy, mix, static_cast<hipStream_t>(hip_stream)));
+}
+
+mxfp4_status mxfp4_tile_copy(const void *src, void *dst, int64_t rows, int64_t row_bytes, void *hip_stream)
+{
+    if (rows < 0 || row_bytes < 0 || rows % 256 != 0 || row_bytes % 128 != 0 || rows >= kMaxRows ||
+        row_bytes > ((int64_t)1 << 23) || (rows / 256) * (row_bytes / 128) >= ((int64_t)1 << 31))
+        return MXFP4_ERR_SHAPE;
+    if (rows == 0 || row_bytes == 0)
+        return MXFP4_OK;
+    if (!src || !dst)
+        return MXFP4_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_tile_copy(src, dst, rows, row_bytes, static_cast<hipStream_t>(hip_stream)));
+}
+
+mxfp4_status mxfp4_record_fanout(const void *src, int64_t ld_src, const int32_t *dst_idx, int64_t M_src, int32_t fanout,
+                                 int64_t rec_bytes, int64_t M_out, void *dst, void *hip_stream)
+{
+    if (M_src < 0 || M_out < 0 || fanout < 1 || rec_bytes <= 0 || rec_bytes % 16 != 0 || rec_bytes > 48 * 1024 ||
+        ld_src < rec_bytes || M_src >= kMaxRows || M_out >= kMaxRows)
+        return MXFP4_ERR_SHAPE;
+    if (M_src == 0 || M_out == 0)
+        return MXFP4_OK;
+    if (!src || !dst || !dst_idx)
+        return MXFP4_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16) || ld_src % 16 != 0 || !aligned(dst_idx, 4))
+        return MXFP4_ERR_ALIGN;
+    return launched(mxfp4::launch_record_fanout(src, ld_src, dst_idx, M_src, fanout, rec_bytes, M_out, dst,
+                                                static_cast<hipStream_t>(hip_stream)));
 }
 
 const char *mxfp4_status_string(mxfp4_status status)

@@ -41,8 +41,15 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
 // 256 if the runtime cannot say): launch heuristics are stated in tiles per compute unit.
 uint32_t compute_units();
 
-// Plain 16-byte-per-lane copy of `bytes` (a multiple of 16) bytes; policy bit 0 = non-temporal loads,
-// bit 1 = non-temporal stores.
-hipError_t launch_stream_copy(const void *src, void *dst, int64_t bytes, int32_t policy, hipStream_t stream);
+// Byte movers without arithmetic (the measured roofs).  `chunks` = work items of the stream mover (16 bytes of
+// the wider side each); policy bit 0 = non-temporal loads, bit 1 = non-temporal stores; mix 0 = 1:1 copy,
+// 1 = 2:1 (16 bytes read, 8 written), 2 = 1:2 (8 read, 16 written), 3 = read only.
+hipError_t launch_stream_copy(const void *src, void *dst, int64_t chunks, int32_t policy, int32_t mix,
+                              hipStream_t stream);
+// A [rows, row_bytes] byte matrix moved tile by tile into the [2 * row_bytes, rows / 2] layout.
+hipError_t launch_tile_copy(const void *src, void *dst, int64_t rows, int64_t row_bytes, hipStream_t stream);
+// Record i of src (rec_bytes at src + i * ld_src) written to the records dst_idx[i * fanout + j] of dst.
+hipError_t launch_record_fanout(const void *src, int64_t ld_src, const int32_t *dst_idx, int64_t M_src, int32_t fanout,
+                                int64_t rec_bytes, int64_t M_out, void *dst, hipStream_t stream);
 
 } // namespace mxfp4

@@ -184,7 +184,10 @@ __device__ __noinline__ uint64_t requant_slice_int(const uint8_t *src, size_t sr
 //    and per k-row: 40 % of the requests to the L2), 3 us would be their share.  Without the column-scale
 //    stores 88 us, without the row-scale loads 90 us.  Merging the pieces of four tiles into one 32-byte request
 //    gained 3.7 us on the loads and nothing on the stores; row scales through scalar loads (one 8-byte
-//    s_load per row, dealt to the lanes with v_writelane): 94-97 us.
+//    s_load per row, dealt to the lanes with v_writelane): 94-97 us.  Workgroups of 512 lanes that take two
+//    tiles next to each other along k, each half in its own LDS as here, with one 16-byte request for the row
+//    scales of both: 98 us against 90 (the bare mover with the scale traffic gains 3 us from that request
+//    shape; two 74 KB workgroups per CU and barriers over eight waves lose more).
 //  * Plain instead of non-temporal stores for the k-rows: 104 us (they only pay when the output is rewritten
 //    in place and stays in the cache: 89 against 93 us); write-through (sc1, sc0 sc1): 103 us; non-temporal
 //    column-scale stores: 142 us; non-temporal row-scale loads: 128 us.

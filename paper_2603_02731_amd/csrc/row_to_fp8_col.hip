@@ -25,14 +25,14 @@
 
 namespace mxfp4 {
 
-// Macro block of the tile order: 16 x 4 tiles (32 x 4 is as fast on one big matrix, 16 x 4 is 4-5 % faster on
-// experts of 2048 or 4096 rows, whose row tiles then fill whole macro blocks; 8 x 4: 165 us against 127 at
-// [65536,7168]; 2 or 8 k-tiles: no difference).  Measured and not built: a lane owning 16 rows with 512 lanes per
+// Macro block of the tile order: 32 x 4 tiles (over rotated buffers at [65536,7168] 127.5 us, 16 x 4 129 us,
+// 8 x 4 164 us; 2 or 8 k-tiles: no difference; on experts of 512 to 4096 rows, whose macro blocks end with
+// the expert, 16 and 32 row tiles are equally fast).  Measured and not built: a lane owning 16 rows with 512 lanes per
 // tile (142 us), the tile leaving in 2 or 4 LDS passes for more workgroups per CU (146-162 us), k-fastest tile order
 // (144 us), plain instead of non-temporal stores for the 256-byte output rows (145 us over rotated buffers).
 namespace fp8col {
 
-constexpr uint32_t MBM = 16, MBK = 4; // macro block of the tile order
+constexpr uint32_t MBM = 32, MBK = 4; // macro block of the tile order
 constexpr int RPL = 32;              // rows of a lane's slice
 constexpr int TILE_M = 256;
 constexpr int TILE_K = 256;

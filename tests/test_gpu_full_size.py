@@ -248,3 +248,30 @@ def test_large_grids_with_inputs_on_4_byte_boundaries():
             wx, wxs = par.row_to_fp8_col(qh, sfh, requant=requant)
             assert_same(host(xs), wxs, f"FP8 column scales, input at +{shift}, requant={requant}")
             assert_same(host(x), wx, f"FP8 column bytes, input at +{shift}, requant={requant}")
+
+
+@pytest.mark.parametrize("M,K", [(32768, 4224), (32768, 4352), (32768, 4480), (24576 + 64, 5760)])
+def test_large_grids_with_odd_numbers_of_column_tiles(M, K):
+    """Grids of more than 2048 tiles (the launch form with 16-byte loads) whose K leaves an odd number of
+    256-column tiles, a 128-column tile at the end, or both, the last with a row count that is not a multiple
+    of the tile; scale bytes that force the integer path and NaN scales are strewn in.  Dense, and the same rows
+    as 24 experts of unequal length."""
+    q, sf = synth.random_mxfp4(M, K, seed=M + K, scale_center=118, scale_spread=9, nan_scale_frac=0.0003)
+    sf[5::997, 3::7] = 254
+    sf[11::1499, K // 32 - 1] = 253
+    sfd, qd = sf.to(DEV), q.to(DEV)
+    qc, sc = mx.mxfp4_row_to_col(qd, sfd)
+    wqc, wsc = par.row_to_col(q.numpy(), sf.numpy())
+    assert_same(host(sc), wsc, f"column scale bytes [{M},{K}]")
+    assert_same(host(qc), wqc, f"column nibbles [{M},{K}]")
+    # the same rows as 24 experts of unequal length (each a multiple of 32 rows)
+    cuts = np.sort(np.random.default_rng(K).choice(np.arange(1, M // 32), 23, replace=False)) * 32
+    off = np.concatenate([[0], cuts, [M]]).astype(np.int32)
+    gq, gs = mx.mxfp4_row_to_col_grouped(qd, sfd, torch.from_numpy(off).to(DEV), offsets_host=off)
+    gq, gs = host(gq), host(gs)
+    for e in range(24):  # whole 32-row blocks per expert: its matrix is its columns of the flat result
+        lo, hi = int(off[e]), int(off[e + 1])
+        assert_same(gs[K * lo // 32: K * hi // 32].reshape(K, (hi - lo) // 32), wsc[:, lo // 32: hi // 32],
+                    f"expert {e} column scale bytes [{M},{K}]")
+        assert_same(gq[K * lo // 2: K * hi // 2].reshape(K, (hi - lo) // 2), wqc[:, lo // 2: hi // 2],
+                    f"expert {e} column nibbles [{M},{K}]")
