@@ -58,7 +58,10 @@ enum {
  * round-to-nearest, ties-to-even onto E2M1 with gradual underflow and saturation; applied
  * directly to the FP8 element values fl32(e4m3 * scale), no BF16 intermediate).
  *   x          E4M3 [M_src, K], 16-byte aligned
- *   x_scale    FP32 [M_src, K/128], 4-byte aligned
+ *   x_scale    FP32 [M_src, K/128], 4-byte aligned.  Blockwise FP8 carries finite positive scales; any other
+ *              FP32 value acts through the IEEE-754 product: a NaN scale, or an infinite one times a zero
+ *              element, makes the element NaN (block scale 0xFF, codes 0), an infinite one times a non-zero
+ *              element overflows (block scale 254, code 7), a negative one flips the signs.
  *   gather_idx NULL: M_out must equal M_src and row i <- row i.
  *              else int32 [M_out] on the device: row i <- row gather_idx[i]
  *              (quantization placed right before the dispatch: the routing gather is fused).

@@ -136,6 +136,8 @@ static unsigned quantize_block32(const double *v, int has_nan, unsigned char *co
  * otherwise from row gather_idx[i].
  * The value of an element is its blockwise-FP8 dequantized FP32 value fl32(e4m3 * s):
  * one rounding to FP32, subnormals kept; section 3.1's quantizer is applied to it.
+ * The product follows IEEE-754 also for scales outside the format's range: a NaN scale, or an
+ * infinite scale times a zero element, gives a NaN element (which poisons its block like a NaN code).
  * Packing: byte j of a row holds element 2j in bits 3..0 and element 2j+1 in bits 7..4. */
 int mxfp4_ref_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_src, int64_t K,
                              const int32_t *gather_idx, int64_t M_out, uint8_t *q, int64_t ld_q,
@@ -167,6 +169,11 @@ int mxfp4_ref_quant_from_fp8(const uint8_t *x, const float *x_scale, int64_t M_s
                 }
                 double a = e4m3_magnitude(c & 0x7Fu);
                 float p = (float)(a * s); /* the product is exact in double; one rounding to FP32 */
+                if (isnan(p)) { /* NaN scale, or 0 * inf */
+                    has_nan = 1;
+                    v[e] = 0.0;
+                    continue;
+                }
                 v[e] = (c & 0x80u) ? -(double)p : (double)p;
             }
             unsigned char code[32];

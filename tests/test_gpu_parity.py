@@ -123,6 +123,33 @@ def test_quant_nan_inf_zero_blocks():
     check_quant(x8, s)
 
 
+def test_quant_scales_outside_the_format():
+    """Tile scales no blockwise-FP8 producer emits: infinite, NaN, negative, negative zero, negative subnormal.
+    The element is the IEEE-754 product, so a NaN scale and infinity times a zero code poison their blocks."""
+    rng = np.random.default_rng(9)
+    x8 = rng.integers(0, 256, (64, 512), dtype=np.int64).astype(np.uint8)
+    x8[::2][(x8[::2] & 0x7F) == 0] = 0x21         # even rows hold no zero codes
+    x8[(x8 & 0x7F) == 0x7F] = 0x42                # NaN codes have their own test
+    exotic = np.array([np.inf, -np.inf, np.nan, -1.0, -0.0, -3.5e-40, -2.0 ** 100, 1.0], np.float32)
+    s = exotic[rng.integers(0, len(exotic), (64, 4))]
+    check_quant(x8, s)
+    q, sf = check_quant(x8, np.full((64, 4), np.inf, np.float32))
+    assert (sf[::2] == 254).all() and ((sf[1::2] == 254) | (sf[1::2] == 255)).all() and (sf[1::2] == 255).any()
+    # the routed forms of the kernel
+    idx = rng.integers(0, 64, 200).astype(np.int32)
+    gq, gsf = mx.mxfp4_quant_from_fp8(dev(x8), dev(s), gather_idx=dev(idx))
+    wq, wsf = ref.quant_from_fp8(x8, s, gather_idx=idx)
+    assert_same(host(gsf), wsf, "gathered scale bytes")
+    assert_same(host(gq), wq, "gathered nibbles")
+    dst = rng.permutation(64 * 3).astype(np.int32).reshape(64, 3)
+    sq, ssf = mx.mxfp4_quant_from_fp8_scatter(dev(x8), dev(s), dev(dst), 64 * 3)
+    inv = np.empty(64 * 3, np.int32)
+    inv[dst.reshape(-1)] = np.repeat(np.arange(64, dtype=np.int32), 3)
+    wq, wsf = ref.quant_from_fp8(x8, s, gather_idx=inv)
+    assert_same(host(ssf), wsf, "scattered scale bytes")
+    assert_same(host(sq), wq, "scattered nibbles")
+
+
 # ------------------------------------------------------------------ dequant
 
 @pytest.mark.parametrize("center,spread,nan", [(127, 0, 0.0), (127, 3, 0.0), (120, 9, 0.01), (60, 25, 0.0),

@@ -199,6 +199,10 @@ MISTAKES = [
      'int64_t r = gather_idx ? (int64_t)gather_idx[i] : i;',
      'int64_t r = gather_idx ? i % M_src : i;', 0,
      ['test_oracle_quant:test_gather_and_strides', 'test_oracle_quant:test_scatter_is_the_gather_turned_around']),
+    ('a NaN product (NaN scale, infinity times zero) counted as zero instead of poisoning its block',
+     'if (isnan(p)) { /* NaN scale, or 0 * inf */\n                    has_nan = 1;',
+     'if (isnan(p)) { /* NaN scale, or 0 * inf */\n                    has_nan = 0;', 0,
+     ['test_oracle_quant:test_scales_outside_the_format_follow_ieee_products']),
 ]
 
 

@@ -219,3 +219,40 @@ def test_scatter_is_the_gather_turned_around():
     assert named.sum() == M * fan - 2
     assert (q[named] == wq[named]).all() and (sf[named] == wsf[named]).all()
     assert (q[~named] == q0[~named]).all() and (sf[~named] == sf0[~named]).all()
+
+
+def test_scales_outside_the_format_follow_ieee_products():
+    """FP32 tile scales that no blockwise-FP8 producer emits.  The element value is the IEEE-754 product
+    fl32(e4m3 * s), here taken with numpy's float32 multiply: NaN (a NaN scale, or an infinite scale times a zero
+    code) poisons the block (byte 0xFF, codes 0); +-inf gives byte 254 and code 7 with the product's sign; a
+    negative finite scale only flips the signs."""
+    rng = np.random.default_rng(5)
+    row = rng.integers(0, 256, 256, dtype=np.int64).astype(np.uint8)
+    row[(row & 0x7F) == 0x7F] = 0x3A            # no NaN codes
+    row[0:32][(row[0:32] & 0x7F) == 0] = 0x11  # block 0 of tile 0: no zeros
+    row[40] = 0x00                              # block 1: a zero
+    row[70] = 0x80                              # block 2: a negative zero
+    row[96:128][(row[96:128] & 0x7F) == 0] = 0x95  # block 3: no zeros
+    x = np.stack([row, row])
+    e4m3 = np.array([(-1.0 if c & 0x80 else 1.0) * float(bf.e4m3_fraction(int(c) & 0x7F)) for c in row], np.float32)
+    for s in (np.inf, -np.inf, np.nan):
+        q, sf = ref.quant_from_fp8(x, np.array([[s, 1.0], [1.0, s]], np.float32))
+        nib = unpack_nibbles(q)
+        with np.errstate(invalid="ignore"):
+            p = e4m3[:128] * np.float32(s)
+        for blk in range(4):
+            pv = p[32 * blk: 32 * blk + 32]
+            got_sf, got = sf[0, blk], nib[0, 32 * blk: 32 * blk + 32]
+            if np.isnan(pv).any():
+                assert got_sf == 0xFF and (got == 0).all(), (s, blk)
+            else:
+                assert got_sf == 254, (s, blk)
+                assert np.array_equal(got, np.where(np.signbit(pv), 0xF, 0x7)), (s, blk)
+        # the other row: tile 1 carries the scale, tile 0 (scale 1) is untouched by it
+        q1, sf1 = ref.quant_from_fp8(x, np.ones((2, 2), np.float32))
+        assert np.array_equal(sf[1, :4], sf1[1, :4]) and np.array_equal(q[1, :64], q1[1, :64])
+    qa, sfa = ref.quant_from_fp8(x, np.full((2, 2), 0.375, np.float32))
+    qb, sfb = ref.quant_from_fp8(x, np.full((2, 2), -0.375, np.float32))
+    assert np.array_equal(sfa, sfb)
+    na, nb = unpack_nibbles(qa), unpack_nibbles(qb)
+    assert np.array_equal(na ^ 8, nb)
