@@ -420,6 +420,30 @@ def test_grouped_more_experts_than_a_wave():
     assert_same(host(x), wx, "150 experts row->FP8 col bytes")
 
 
+def test_grouped_tile_order_over_many_experts_and_column_tiles():
+    """200 experts in four lane-parallel steps of the lookup, three column tiles, lengths from empty to more
+    row tiles than a macro block of the tile order holds (9000 rows = 36 tiles): every tile of every expert has
+    to be visited exactly once by the order that walks macro blocks inside each expert."""
+    rng = np.random.default_rng(77)
+    kinds = [0, 0, 1, 31, 32, 33, 127, 128, 129, 255, 256, 257, 511, 513, 1025]
+    counts = rng.choice(kinds, size=200)
+    counts[17], counts[130] = 9000, 8192 + 256
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    M, K = int(off[-1]), 768
+    q, sf = synth.random_mxfp4(M, K, seed=78, scale_center=121, scale_spread=6, nan_scale_frac=0.0005)
+    q, sf = q.numpy(), sf.numpy()
+    offd = torch.from_numpy(off).to(DEV)
+    qc, sc = mx.mxfp4_row_to_col_grouped(dev(q), dev(sf), offd, offsets_host=off)
+    wqc, wsc = ref.row_to_col_grouped(q, sf, off)
+    assert_same(host(sc), wsc, "200 experts row->col scales")
+    assert_same(host(qc), wqc, "200 experts row->col nibbles")
+    for requant in (False, True):
+        x, xs = mx.mxfp4_row_to_fp8_col_grouped(dev(q), dev(sf), offd, requant=requant, offsets_host=off)
+        wx, wxs = ref.row_to_fp8_col_grouped(q, sf, off, requant=requant)
+        assert_same(host(xs), wxs, f"200 experts row->FP8 col scales, requant={requant}")
+        assert_same(host(x), wx, f"200 experts row->FP8 col bytes, requant={requant}")
+
+
 def test_grouped_with_the_largest_number_of_experts():
     # 1024 experts, the most the C ABI takes (16 lane-parallel steps of the lookup): ragged sizes 0..300,
     # many empty, the first and last experts of every step of 64 non-empty
