@@ -1,7 +1,9 @@
 """GPU parity on seeded random shapes: every entry point against the CPU oracle, bit for bit, on
 shapes and expert splits that no other test fixes by hand (tiles of 128 and 256 columns, partial
 row tiles, odd split lengths, empty experts, unaligned k-rows), with guard bytes around every
-output of the ragged forms."""
+output of the ragged forms.  MXFP4_EXTRA_SEEDS=n in the environment adds n further seeds to each test."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -13,6 +15,7 @@ from paper_2603_02731_amd import synth
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 GUARD = 1024
+EXTRA = int(os.environ.get("MXFP4_EXTRA_SEEDS", "0"))
 
 
 def dev(a):
@@ -56,7 +59,7 @@ def random_splits(rng, total_cap):
     return T
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(12 + EXTRA))
 def test_flat_entry_points_on_random_shapes(seed):
     rng = np.random.default_rng(1000 + seed)
     M = 32 * int(rng.integers(1, 40))            # row->col needs M % 32 == 0
@@ -84,7 +87,7 @@ def test_flat_entry_points_on_random_shapes(seed):
             same(host(xc), wxc, f"row->FP8 col bytes [{M},{K}] requant={requant}")
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(12 + EXTRA))
 def test_grouped_entry_points_on_random_splits(seed):
     rng = np.random.default_rng(2000 + seed)
     K = 128 * int(rng.integers(1, 7))
@@ -112,7 +115,7 @@ def test_grouped_entry_points_on_random_splits(seed):
         same(check_guards(xbuf, wx.size, 0xA5, "x_col"), wx, f"grouped FP8 col bytes T={T} K={K} requant={requant}")
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(10 + EXTRA))
 def test_strided_and_routed_forms_on_random_shapes(seed):
     """The non-dense kernel instances: gathered rows into padded planes and into per-token records, the
     de-quantizer reading those, the scatter form with a random fan-out, the BF16 quantizer into padded
