@@ -364,6 +364,11 @@ def main():
             if "cold" in kernels[k]:
                 kernels[k]["cold"]["frac_of_measured_copy"] = kernels[k]["cold"]["GB/s"] / best
                 kernels[k]["cold"]["frac_of_its_mover"] = kernels[k]["cold"]["GB/s"] / out["movers"][k]["GB/s"]
+        if "roofline" in out:  # the same kernel against a kernel that only moves its bytes in its access pattern
+            w = out["roofline"]["kernel"]
+            out["roofline"]["mover"] = {"what": out["movers"][w]["what"], "GB/s": out["movers"][w]["GB/s"],
+                                        "frac_of_hbm_peak": out["movers"][w]["frac_of_hbm_peak"],
+                                        "kernel_rate_over_mover_rate": kernels[w]["cold"]["frac_of_its_mover"]}
         for t in S:  # the movers wrote over the MXFP4 and FP8 outputs: every set holds valid data again
             quant(t), dequant(t), row_to_col(t)
         torch.cuda.synchronize()
