@@ -101,10 +101,13 @@ __device__ __forceinline__ float row_scale_operand(const uint32_t (&sb)[8])
 
 // Workgroup -> tile for the transposing kernels.  The hardware deals consecutive workgroup ids
 // round-robin to the 8 XCDs, each with its own L2.  Id i therefore takes entry i/8 of XCD (i%8)'s
-// own contiguous share of a tile order in which MBM x MBK tiles form a macro block walked
+// own contiguous share of a tile order in which mbm x MBK tiles form a macro block walked
 // m-fastest: the tiles an XCD has in flight together are neighbours along m (their output pieces
 // and their few-byte scale pieces complete whole lines in that L2) and along k (they share the
 // 32-byte sectors of the row scales).  Returns false for the ids that round the grid up.
+// mbm is chosen by the launch (macro_block_rows) so that an XCD's share is a whole number of macro
+// rows: every XCD then walks its own band of row tiles from the first k tile to the last, all of
+// them are at the same k at the same time, and the chip writes whole rows of the output together.
 constexpr uint32_t NUM_XCD = 8;
 __device__ __forceinline__ bool order_entry_of_workgroup(uint32_t id, uint32_t total, uint32_t *entry)
 {
@@ -114,9 +117,9 @@ __device__ __forceinline__ bool order_entry_of_workgroup(uint32_t id, uint32_t t
 }
 
 // Entry l of the macro-block walk over tiles_m x tiles_k tiles.
-template <uint32_t MBM, uint32_t MBK>
-__device__ __forceinline__ void tile_of_order_entry(uint32_t l, uint32_t tiles_m, uint32_t tiles_k, uint32_t *tile_m,
-                                                    uint32_t *tile_k)
+template <uint32_t MBK>
+__device__ __forceinline__ void tile_of_order_entry(uint32_t l, uint32_t tiles_m, uint32_t tiles_k, uint32_t MBM,
+                                                    uint32_t *tile_m, uint32_t *tile_k)
 {
     const uint32_t per_macro_row = MBM * tiles_k;
     const uint32_t mg = l / per_macro_row;
@@ -129,15 +132,29 @@ __device__ __forceinline__ void tile_of_order_entry(uint32_t l, uint32_t tiles_m
     *tile_k = kg * MBK + k_in;
 }
 
-template <uint32_t MBM, uint32_t MBK>
-__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k,
+template <uint32_t MBK>
+__device__ __forceinline__ bool tile_of_workgroup(uint32_t id, uint32_t tiles_m, uint32_t tiles_k, uint32_t mbm,
                                                   uint32_t *tile_m, uint32_t *tile_k)
 {
     uint32_t l;
     if (!order_entry_of_workgroup(id, tiles_m * tiles_k, &l))
         return false;
-    tile_of_order_entry<MBM, MBK>(l, tiles_m, tiles_k, tile_m, tile_k);
+    tile_of_order_entry<MBK>(l, tiles_m, tiles_k, mbm, tile_m, tile_k);
     return true;
+}
+
+// Row tiles per macro block for a matrix of tiles_m row tiles: an eighth of them, one band per XCD; halved
+// while it exceeds 64 (a share is then 2, 4, ... macro rows).  Measured with row_to_col at K = 7168 over rotated
+// buffers against a fixed 32: M = 49152 0.63 -> 0.67 of the HBM peak, 61440 0.58 -> 0.67, 73728 0.62 -> 0.685,
+// 98304 0.67 -> 0.69; 65536 and 131072 (where an eighth, or a sixteenth, is 32) unchanged; a quarter or a
+// sixteenth of the row tiles instead of an eighth: 1-4 % behind wherever they differ from this rule's choice,
+// 6-18 % at M = 65536 and 131072.
+inline uint32_t macro_block_rows(uint32_t tiles_m)
+{
+    uint32_t b = (tiles_m + NUM_XCD - 1) / NUM_XCD;
+    while (b > 64u)
+        b = (b + 1u) / 2u;
+    return b ? b : 1u;
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave, in the lanes' own registers (DPP): a scan
@@ -223,7 +240,7 @@ __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, in
             *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo[c], l);
             *rows = (uint32_t)__builtin_amdgcn_readlane((int)len, l);
             const uint32_t nt_e = (uint32_t)__builtin_amdgcn_readlane((int)nt, l);
-            tile_of_order_entry<MBM, MBK>(entry - (before + excl) * tiles_k, nt_e, tiles_k, tile_m, tile_k);
+            tile_of_order_entry<MBK>(entry - (before + excl) * tiles_k, nt_e, tiles_k, MBM, tile_m, tile_k);
             if (UNIT_A)
                 *a_before = abefore + (uint32_t)__builtin_amdgcn_readlane((int)(aincl - na), l);
             if (UNIT_B)

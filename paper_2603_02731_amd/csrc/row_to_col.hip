@@ -45,10 +45,12 @@ struct RowToColArgs {
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
+    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts use MBM)
 };
 
-// Macro block of the tile order: 32 row tiles (the CUs of an XCD) x 4 column tiles.  Over rotated buffers at
-// [65536,7168]: 8 / 16 / 64 row tiles 103 / 108 / 98 us against 93; 1, 2, 7, 14 or 28 column tiles no difference.
+// Macro block of the tile order: 4 column tiles; row tiles by macro_block_rows for one matrix (32 at
+// [65536,7168], where over rotated buffers 8 / 16 / 64 row tiles took 103 / 108 / 98 us against 93 and 1, 2, 7, 14
+// or 28 column tiles made no difference), at most MBM inside an expert of a grouped launch.
 constexpr uint32_t MBM = 32, MBK = 4;
 
 // The nibbles are read once: non-temporal loads.
@@ -214,7 +216,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
                                                                 &strip, &tile_k, &row_base, &rows, &bytes_before,
                                                                 &blocks_before))
             return;
-    } else if (!tile_of_workgroup<MBM, MBK>(blockIdx.x, a.tiles_m, a.tiles_k, &strip, &tile_k)) {
+    } else if (!tile_of_workgroup<MBK>(blockIdx.x, a.tiles_m, a.tiles_k, a.mbm, &strip, &tile_k)) {
         return;
     }
     const uint32_t m0 = strip * TILE_M;
@@ -458,6 +460,7 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     // upper bound on the number of row tiles: every expert may end in a partial one
     a.tiles_m = (uint32_t)((M + TILE_M - 1) / TILE_M + (expert_offsets ? num_experts : 0));
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
+    a.mbm = macro_block_rows(a.tiles_m);
     const uint32_t total = a.tiles_m * a.tiles_k;
     a.stage_in = total >= 8u * compute_units() ? 1u : 0u; // at least 8 tiles per compute unit
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);

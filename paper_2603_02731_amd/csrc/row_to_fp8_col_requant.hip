@@ -44,6 +44,7 @@ struct Args {
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
+    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts use 32)
 };
 
 // Emax = biased exponent of a non-zero column maximum, plus one (FP32 subnormals: 2^-127 and
@@ -132,7 +133,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
         if (!tile_of_grouped_workgroup<TILE_M, 128, 0, 32, 4>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
                                                               &tile_m, &tile_k, &row_base, &rows, &groups_before))
             return;
-    } else if (!tile_of_workgroup<32, 4>(blockIdx.x, a.tiles_m, a.tiles_k, &tile_m, &tile_k)) {
+    } else if (!tile_of_workgroup<4>(blockIdx.x, a.tiles_m, a.tiles_k, a.mbm, &tile_m, &tile_k)) {
         return;
     }
     const uint32_t m0 = tile_m * TILE_M; // first row of the tile inside its group
@@ -400,6 +401,7 @@ hipError_t launch_row_to_fp8_col_requant(const uint8_t *q_row, const uint8_t *sf
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     const uint32_t total = a.tiles_m * a.tiles_k;
     a.stage_in = total >= 8u * compute_units() ? 1u : 0u; // at least 8 tiles per compute unit
+    a.mbm = macro_block_rows(a.tiles_m);
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_fp8_col_requant_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();

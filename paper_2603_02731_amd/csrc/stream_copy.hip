@@ -92,10 +92,10 @@ hipError_t launch_stream_copy(const void *src, void *dst, int64_t chunks, int32_
 
 constexpr int TC_THREADS = 256;
 __global__ void __launch_bounds__(TC_THREADS) tile_copy_kernel(const uint8_t *src, uint8_t *dst, uint32_t rows,
-                                                               uint32_t row_bytes, uint32_t tiles_m, uint32_t tiles_k)
+                                                               uint32_t row_bytes, uint32_t tiles_m, uint32_t tiles_k, uint32_t mbm)
 {
     uint32_t tm, tk;
-    if (!tile_of_workgroup<32, 4>(blockIdx.x, tiles_m, tiles_k, &tm, &tk))
+    if (!tile_of_workgroup<4>(blockIdx.x, tiles_m, tiles_k, mbm, &tm, &tk))
         return;
     const uint32_t tid = threadIdx.x;
     const size_t pin = row_bytes, pout = rows / 2u; // output: 2 * row_bytes rows of rows / 2 bytes
@@ -120,7 +120,7 @@ hipError_t launch_tile_copy(const void *src, void *dst, int64_t rows, int64_t ro
     const uint32_t tiles_m = (uint32_t)(rows / 256), tiles_k = (uint32_t)(row_bytes / 128), total = tiles_m * tiles_k;
     hipLaunchKernelGGL(tile_copy_kernel, dim3((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD), dim3(TC_THREADS), 0, stream,
                        static_cast<const uint8_t *>(src), static_cast<uint8_t *>(dst), (uint32_t)rows,
-                       (uint32_t)row_bytes, tiles_m, tiles_k);
+                       (uint32_t)row_bytes, tiles_m, tiles_k, macro_block_rows(tiles_m));
     return hipGetLastError();
 }
 
