@@ -28,7 +28,8 @@
  *   - NaN: an E4M3 NaN makes its MXFP4 block's scale byte 0xFF and its 16 packed bytes 0;
  *     a 0xFF scale byte makes the FP8 tile scale NaN and its block's 32 bytes 0x7F; in the
  *     row->column conversion it makes every column block it touches 0xFF / 0.
- *     FP32 tile scales must be finite and >= 0.
+ *     Blockwise FP8 carries finite positive FP32 tile scales; what any other value does is stated at
+ *     mxfp4_quant_from_fp8 (the IEEE-754 product decides).
  */
 #ifndef MXFP4_H
 #define MXFP4_H
