@@ -178,7 +178,9 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 // into the next expert continues at an unrelated address; measured with a kernel that only moves
 // the nibbles of 32 experts of 2048 rows, K = 7168, every byte from and to HBM: 84 us with the
 // macro blocks inside the experts, 96 us with 32 concatenated row tiles per block; 83 against 103 us
-// at 512 rows per expert).  The XCD shares are cut from this order with the number of tiles that
+// at 512 rows per expert).  An expert that extends over several XCD shares gets macro blocks of its width over
+// that number (mover: one expert of 61440 rows 95 -> 76 us, two of 30720 81 -> 76, the Zipf-sized and the equal
+// experts of the configurations unchanged, three of 21760 82 -> 85).  The XCD shares are cut from this order with the number of tiles that
 // really exist (the launch can only bound it: with the bound in its place the ids that round the
 // grid up would all fall into the last XCD's share and the others would carry its tiles).
 // Uniform per workgroup; every wave evaluates it on its own, 64 experts per lane-parallel step:
@@ -188,7 +190,7 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
 // `a_before` / `b_before` the sum of ceil(T_j / UNIT) over the experts before it (where its
 // outputs start when the splits are not padded).
 constexpr int MAX_EXPERT_CHUNKS = 16; // 64 experts each: MXFP4_MAX_EXPERTS of the C ABI
-template <uint32_t TILE_ROWS, uint32_t UNIT_A, uint32_t UNIT_B, uint32_t MBM, uint32_t MBK>
+template <uint32_t TILE_ROWS, uint32_t UNIT_A, uint32_t UNIT_B, uint32_t MBM_MAX, uint32_t MBK>
 __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, int32_t num_experts, uint32_t id,
                                                           uint32_t tiles_k, uint32_t *tile_m, uint32_t *tile_k,
                                                           uint32_t *row_base, uint32_t *rows,
@@ -240,7 +242,17 @@ __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, in
             *row_base = (uint32_t)__builtin_amdgcn_readlane((int)lo[c], l);
             *rows = (uint32_t)__builtin_amdgcn_readlane((int)len, l);
             const uint32_t nt_e = (uint32_t)__builtin_amdgcn_readlane((int)nt, l);
-            tile_of_order_entry<MBK>(entry - (before + excl) * tiles_k, nt_e, tiles_k, MBM, tile_m, tile_k);
+            // macro block: the expert's width over the number of XCD shares it extends over (one expert is
+            // then walked like a single matrix, see macro_block_rows), halved while above MBM_MAX
+            // (the divisions only for an expert of at least 1.5 shares: every workgroup waits for this lookup)
+            uint32_t mbm = nt_e;
+            if (2u * NUM_XCD * nt_e >= 3u * total) {
+                const uint32_t spans = (NUM_XCD * nt_e + total / 2u) / total;
+                mbm = (nt_e + spans - 1u) / spans;
+            }
+            while (mbm > MBM_MAX)
+                mbm = (mbm + 1u) / 2u;
+            tile_of_order_entry<MBK>(entry - (before + excl) * tiles_k, nt_e, tiles_k, mbm, tile_m, tile_k);
             if (UNIT_A)
                 *a_before = abefore + (uint32_t)__builtin_amdgcn_readlane((int)(aincl - na), l);
             if (UNIT_B)

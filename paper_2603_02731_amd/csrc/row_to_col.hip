@@ -45,13 +45,13 @@ struct RowToColArgs {
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
-    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts use MBM)
+    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts: see the lookup)
 };
 
 // Macro block of the tile order: 4 column tiles; row tiles by macro_block_rows for one matrix (32 at
 // [65536,7168], where over rotated buffers 8 / 16 / 64 row tiles took 103 / 108 / 98 us against 93 and 1, 2, 7, 14
-// or 28 column tiles made no difference), at most MBM inside an expert of a grouped launch.
-constexpr uint32_t MBM = 32, MBK = 4;
+// or 28 column tiles made no difference), at most MBM_MAX inside an expert of a grouped launch.
+constexpr uint32_t MBM_MAX = 64, MBK = 4;
 
 // The nibbles are read once: non-temporal loads.
 __device__ __forceinline__ uint32_t load_nibbles(const uint32_t *p)
@@ -212,7 +212,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
     uint32_t strip, tile_k;
     uint32_t row_base = 0, rows = a.M, bytes_before = 0, blocks_before = 0;
     if (a.expert_offsets) {
-        if (!tile_of_grouped_workgroup<TILE_M, 2, 32, MBM, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+        if (!tile_of_grouped_workgroup<TILE_M, 2, 32, MBM_MAX, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
                                                                 &strip, &tile_k, &row_base, &rows, &bytes_before,
                                                                 &blocks_before))
             return;

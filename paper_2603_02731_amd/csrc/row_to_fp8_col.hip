@@ -27,13 +27,13 @@ namespace mxfp4 {
 
 // Macro block of the tile order: 4 column tiles; row tiles by macro_block_rows for one matrix (32 at [65536,7168]:
 // over rotated buffers 127.5 us, 16 x 4 129 us, 8 x 4 164 us; 2 or 8 k-tiles: no difference; [61440,7168] 146 -> 124 us
-// against a fixed 32), at most MBM inside an expert (on experts of 512 to 4096 rows, whose macro blocks end with
+// against a fixed 32), at most MBM_MAX inside an expert (on experts of 512 to 4096 rows, whose macro blocks end with
 // the expert, 16 and 32 row tiles are equally fast).  Measured and not built: a lane owning 16 rows with 512 lanes per
 // tile (142 us), the tile leaving in 2 or 4 LDS passes for more workgroups per CU (146-162 us), k-fastest tile order
 // (144 us), plain instead of non-temporal stores for the 256-byte output rows (145 us over rotated buffers).
 namespace fp8col {
 
-constexpr uint32_t MBM = 32, MBK = 4; // macro block of the tile order
+constexpr uint32_t MBM_MAX = 64, MBK = 4; // macro block of the tile order
 constexpr int RPL = 32;              // rows of a lane's slice
 constexpr int TILE_M = 256;
 constexpr int TILE_K = 256;
@@ -52,7 +52,7 @@ struct Args {
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
-    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts use MBM)
+    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts: see the lookup)
 };
 
 // Decode-scale operand of row I of a slice: exponent field max(127 - (bmax - b_I), 0) in bits
@@ -89,7 +89,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_kernel(const Args a)
     uint32_t tile_m, tile_k;
     uint32_t row_base = 0, rows = a.M, groups_before = 0;
     if (a.expert_offsets) {
-        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, MBM, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, MBM_MAX, MBK>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
                                                                  &tile_m, &tile_k, &row_base, &rows, &groups_before))
             return;
     } else if (!tile_of_workgroup<MBK>(blockIdx.x, a.tiles_m, a.tiles_k, a.mbm, &tile_m, &tile_k)) {

@@ -44,7 +44,7 @@ struct Args {
     uint32_t tiles_m; // 256-row tiles (an upper bound when grouped)
     uint32_t tiles_k; // 256-column tiles
     uint32_t stage_in; // full tiles fetch their nibbles with 16-byte loads and re-slice them through LDS
-    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts use 32)
+    uint32_t mbm;      // row tiles per macro block of the tile order (one matrix; experts: see the lookup)
 };
 
 // Emax = biased exponent of a non-zero column maximum, plus one (FP32 subnormals: 2^-127 and
@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(T_THREADS) row_to_fp8_col_requant_kernel(const
     uint32_t tile_m, tile_k;
     uint32_t row_base = 0, rows = a.M, groups_before = 0;
     if (a.expert_offsets) {
-        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, 32, 4>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
+        if (!tile_of_grouped_workgroup<TILE_M, 128, 0, 64, 4>(a.expert_offsets, a.num_experts, blockIdx.x, a.tiles_k,
                                                               &tile_m, &tile_k, &row_base, &rows, &groups_before))
             return;
     } else if (!tile_of_workgroup<4>(blockIdx.x, a.tiles_m, a.tiles_k, a.mbm, &tile_m, &tile_k)) {
