@@ -244,7 +244,7 @@ __device__ __forceinline__ bool tile_of_grouped_workgroup(const int32_t *off, in
             const uint32_t nt_e = (uint32_t)__builtin_amdgcn_readlane((int)nt, l);
             // macro block: the expert's width over the number of XCD shares it extends over (one expert is
             // then walked like a single matrix, see macro_block_rows), halved while above MBM_MAX
-            // (the divisions only for an expert of at least 1.5 shares: every workgroup waits for this lookup)
+            // (the divisions only for an expert of at least 1.5 shares)
             uint32_t mbm = nt_e;
             if (2u * NUM_XCD * nt_e >= 3u * total) {
                 const uint32_t spans = (NUM_XCD * nt_e + total / 2u) / total;
