@@ -282,8 +282,10 @@ __global__ void __launch_bounds__(T_THREADS) row_to_col_kernel(const RowToColArg
     };
     // With many tiles per CU a full tile arrives through 16-byte loads (8 rows x 128 bytes per wave
     // instruction instead of 2) and is cut into the lanes' 32 x 8 slices through the tile buffer: a wave
-    // fetches the 64 rows of its own two row groups, row-major.  At [65536,7168] 93 us against 95; with few
-    // tiles per CU the extra barrier and LDS round trip cost 6 %, so the launcher asks for it only on large grids.
+    // fetches the 64 rows of its own two row groups, row-major.  At [65536,7168] 93 us against 95.  Over rotated
+    // buffers the dword loads win up to 640 tiles by 1-3 % ([16384,2048] 9.3 against 9.7 us), at 768 tiles the two
+    // are equal, from 896 on ([8192,7168], [32768,2048], [16384,4096]) the 16-byte loads win by 6-8 %: the launcher
+    // asks for them from three tiles per compute unit on.
     const bool staged = a.stage_in != 0u && n_rows == (uint32_t)TILE_M && cols == (uint32_t)TILE_K &&
                         (reinterpret_cast<uintptr_t>(a.q_row) & 15u) == 0u;
     u32x4 stage_v[8];
@@ -462,7 +464,7 @@ hipError_t launch_row_to_col(const uint8_t *q_row, const uint8_t *sf_row, const 
     a.tiles_k = (uint32_t)((K + TILE_K - 1) / TILE_K);
     a.mbm = macro_block_rows(a.tiles_m);
     const uint32_t total = a.tiles_m * a.tiles_k;
-    a.stage_in = total >= 8u * compute_units() ? 1u : 0u; // at least 8 tiles per compute unit
+    a.stage_in = total >= 3u * compute_units() ? 1u : 0u; // at least 3 tiles per compute unit
     const dim3 grid((total + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     hipLaunchKernelGGL(row_to_col_kernel, grid, dim3(T_THREADS), 0, stream, a);
     return hipGetLastError();
