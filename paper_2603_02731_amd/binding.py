@@ -89,17 +89,19 @@ def _buf(t, dtype, name, *, shape=None, min_bytes=None):
 
 def _on_device(**tensors):
     """Last check before a launch: every tensor of the call is a HIP device tensor, all on one device (a host
-    address handed to a kernel is a GPU memory fault, not an exception)."""
-    first = None
+    address handed to a kernel is a GPU memory fault, not an exception).  Returns that device's index."""
+    dev = -1
     for name, t in tensors.items():
         if t is None:
             continue
         if not t.is_cuda:
             raise TypeError(f"{name} must be a HIP device tensor, got one on {t.device}")
-        if first is None:
-            first = t
-        elif t.device != first.device:
-            raise ValueError(f"{name} is on {t.device}, the other arguments on {first.device}")
+        d = t.get_device()
+        if dev < 0:
+            dev = d
+        elif d != dev:
+            raise ValueError(f"{name} is on device {d}, the other arguments on device {dev}")
+    return dev
 
 
 def _matrix(t, dtype, name, k_multiple):
@@ -121,9 +123,18 @@ def _strided_out(t, name, rows, row_bytes, ld):
     return _buf(t, torch.uint8, name, min_bytes=need)
 
 
-def _stream(stream):
-    s = torch.cuda.current_stream() if stream is None else stream
-    return s.cuda_stream if hasattr(s, "cuda_stream") else int(s)
+# the raw handle of the current stream of a device, without building a torch.cuda.Stream object (2.7 us a call)
+_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
+def _stream(stream, dev):
+    """The hipStream_t to launch on: the caller's (a torch.cuda.Stream or a raw handle), else the current stream
+    of the tensors' device."""
+    if stream is None:
+        if _raw_current_stream is not None:
+            return _raw_current_stream(dev)
+        return torch.cuda.current_stream(dev).cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
 def _quant_outputs(x, M_out, K, q, sf, ld_q, ld_sf, fill):
@@ -158,10 +169,10 @@ def mxfp4_quant_from_fp8(x, x_scale, gather_idx=None, q=None, sf=None, ld_q=None
     else:
         M_out = M_src
     q, sf, ld_q, ld_sf = _quant_outputs(x, M_out, K, q, sf, ld_q, ld_sf, torch.empty)
-    _on_device(x=x, x_scale=x_scale, gather_idx=gather_idx, q=q, sf=sf)
+    dev = _on_device(x=x, x_scale=x_scale, gather_idx=gather_idx, q=q, sf=sf)
     st = lib().mxfp4_quant_from_fp8(x.data_ptr(), x_scale.data_ptr(), M_src, K,
                                     None if gather_idx is None else gather_idx.data_ptr(), M_out,
-                                    q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream))
+                                    q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream, dev))
     _check("mxfp4_quant_from_fp8", st)
     return q, sf
 
@@ -178,10 +189,10 @@ def mxfp4_quant_from_fp8_scatter(x, x_scale, dst_idx, M_out, q=None, sf=None, ld
     if M_out < 0:
         raise ValueError("M_out must not be negative")
     q, sf, ld_q, ld_sf = _quant_outputs(x, M_out, K, q, sf, ld_q, ld_sf, torch.zeros)
-    _on_device(x=x, x_scale=x_scale, dst_idx=dst_idx, q=q, sf=sf)
+    dev = _on_device(x=x, x_scale=x_scale, dst_idx=dst_idx, q=q, sf=sf)
     st = lib().mxfp4_quant_from_fp8_scatter(x.data_ptr(), x_scale.data_ptr(), M_src, K, dst_idx.data_ptr(),
                                             dst_idx.shape[1], M_out, q.data_ptr(), ld_q, sf.data_ptr(), ld_sf,
-                                            _stream(stream))
+                                            _stream(stream, dev))
     _check("mxfp4_quant_from_fp8_scatter", st)
     return q, sf
 
@@ -190,8 +201,8 @@ def mxfp4_quant_from_bf16(x, q=None, sf=None, ld_q=None, ld_sf=None, stream=None
     """x bfloat16 [M,K] -> (q uint8 [M,K/2], sf uint8 [M,K/32])."""
     M, K = _matrix(x, torch.bfloat16, "x", 128)
     q, sf, ld_q, ld_sf = _quant_outputs(x, M, K, q, sf, ld_q, ld_sf, torch.empty)
-    _on_device(x=x, q=q, sf=sf)
-    st = lib().mxfp4_quant_from_bf16(x.data_ptr(), M, K, q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream))
+    dev = _on_device(x=x, q=q, sf=sf)
+    st = lib().mxfp4_quant_from_bf16(x.data_ptr(), M, K, q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, _stream(stream, dev))
     _check("mxfp4_quant_from_bf16", st)
     return q, sf
 
@@ -223,9 +234,9 @@ def mxfp4_dequant_to_fp8(q, sf, M=None, K=None, ld_q=None, ld_sf=None, x=None, x
         x_scale = torch.empty((M, K // 128), dtype=torch.float32, device=q.device)
     else:
         _buf(x_scale, torch.float32, "x_scale", min_bytes=M * (K // 128) * 4)
-    _on_device(q=q, sf=sf, x=x, x_scale=x_scale)
+    dev = _on_device(q=q, sf=sf, x=x, x_scale=x_scale)
     st = lib().mxfp4_dequant_to_fp8(q.data_ptr(), ld_q, sf.data_ptr(), ld_sf, M, K,
-                                    x.data_ptr(), x_scale.data_ptr(), _stream(stream))
+                                    x.data_ptr(), x_scale.data_ptr(), _stream(stream, dev))
     _check("mxfp4_dequant_to_fp8", st)
     return x, x_scale
 
@@ -271,9 +282,9 @@ def mxfp4_row_to_col(q_row, sf_row, q_col=None, sf_col=None, stream=None):
         raise ValueError(f"M must be a multiple of 32, got {M}")
     q_col = _out(q_col, torch.uint8, "q_col", q_row, (K, M // 2))
     sf_col = _out(sf_col, torch.uint8, "sf_col", q_row, (K, M // 32))
-    _on_device(q_row=q_row, sf_row=sf_row, q_col=q_col, sf_col=sf_col)
+    dev = _on_device(q_row=q_row, sf_row=sf_row, q_col=q_col, sf_col=sf_col)
     st = lib().mxfp4_row_to_col(q_row.data_ptr(), sf_row.data_ptr(), M, K, q_col.data_ptr(),
-                                sf_col.data_ptr(), _stream(stream))
+                                sf_col.data_ptr(), _stream(stream, dev))
     _check("mxfp4_row_to_col", st)
     return q_col, sf_col
 
@@ -283,10 +294,10 @@ def mxfp4_quant_from_fp8_grouped(x, x_scale, expert_offsets, q=None, sf=None, st
     _buf(x_scale, torch.float32, "x_scale", shape=(M, K // 128))
     _experts(expert_offsets, M, None, ())
     q, sf, _, _ = _quant_outputs(x, M, K, q, sf, None, None, torch.empty)
-    _on_device(x=x, x_scale=x_scale, expert_offsets=expert_offsets, q=q, sf=sf)
+    dev = _on_device(x=x, x_scale=x_scale, expert_offsets=expert_offsets, q=q, sf=sf)
     st = lib().mxfp4_quant_from_fp8_grouped(x.data_ptr(), x_scale.data_ptr(), expert_offsets.data_ptr(),
                                             expert_offsets.shape[0] - 1, M, K, q.data_ptr(), sf.data_ptr(),
-                                            _stream(stream))
+                                            _stream(stream, dev))
     _check("mxfp4_quant_from_fp8_grouped", st)
     return q, sf
 
@@ -300,9 +311,9 @@ def mxfp4_row_to_col_grouped(q_row, sf_row, expert_offsets, q_col=None, sf_col=N
     E, (n2, n32) = _experts(expert_offsets, M, offsets_host, (2, 32))
     q_col = _out(q_col, torch.uint8, "q_col", q_row, K * n2)
     sf_col = _out(sf_col, torch.uint8, "sf_col", q_row, K * n32)
-    _on_device(q_row=q_row, sf_row=sf_row, expert_offsets=expert_offsets, q_col=q_col, sf_col=sf_col)
+    dev = _on_device(q_row=q_row, sf_row=sf_row, expert_offsets=expert_offsets, q_col=q_col, sf_col=sf_col)
     st = lib().mxfp4_row_to_col_grouped(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(),
-                                        E, M, K, q_col.data_ptr(), sf_col.data_ptr(), _stream(stream))
+                                        E, M, K, q_col.data_ptr(), sf_col.data_ptr(), _stream(stream, dev))
     _check("mxfp4_row_to_col_grouped", st)
     return q_col, sf_col
 
@@ -315,9 +326,9 @@ def mxfp4_row_to_fp8_col(q_row, sf_row, x_col=None, x_col_scale=None, stream=Non
         raise ValueError(f"M must be a multiple of 128, got {M}")
     x_col = _out(x_col, torch.uint8, "x_col", q_row, (K, M))
     x_col_scale = _out(x_col_scale, torch.float32, "x_col_scale", q_row, (K, M // 128))
-    _on_device(q_row=q_row, sf_row=sf_row, x_col=x_col, x_col_scale=x_col_scale)
+    dev = _on_device(q_row=q_row, sf_row=sf_row, x_col=x_col, x_col_scale=x_col_scale)
     fn = lib().mxfp4_row_to_fp8_col_requant if requant else lib().mxfp4_row_to_fp8_col
-    st = fn(q_row.data_ptr(), sf_row.data_ptr(), M, K, x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream))
+    st = fn(q_row.data_ptr(), sf_row.data_ptr(), M, K, x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream, dev))
     _check("mxfp4_row_to_fp8_col_requant" if requant else "mxfp4_row_to_fp8_col", st)
     return x_col, x_col_scale
 
@@ -331,10 +342,10 @@ def mxfp4_row_to_fp8_col_grouped(q_row, sf_row, expert_offsets, x_col=None, x_co
     E, (n128,) = _experts(expert_offsets, M, offsets_host, (128,))
     x_col = _out(x_col, torch.uint8, "x_col", q_row, M * K)
     x_col_scale = _out(x_col_scale, torch.float32, "x_col_scale", q_row, K * n128)
-    _on_device(q_row=q_row, sf_row=sf_row, expert_offsets=expert_offsets, x_col=x_col, x_col_scale=x_col_scale)
+    dev = _on_device(q_row=q_row, sf_row=sf_row, expert_offsets=expert_offsets, x_col=x_col, x_col_scale=x_col_scale)
     fn = lib().mxfp4_row_to_fp8_col_requant_grouped if requant else lib().mxfp4_row_to_fp8_col_grouped
     st = fn(q_row.data_ptr(), sf_row.data_ptr(), expert_offsets.data_ptr(), E, M, K,
-            x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream))
+            x_col.data_ptr(), x_col_scale.data_ptr(), _stream(stream, dev))
     _check("mxfp4_row_to_fp8_col_requant_grouped" if requant else "mxfp4_row_to_fp8_col_grouped", st)
     return x_col, x_col_scale
 
@@ -357,8 +368,8 @@ def mxfp4_stream_mix(src, dst, mix, policy=3, stream=None):
         raise ValueError("the mover works in whole 16-byte chunks")
     need = {0: wide, 1: wide // 2, 2: wide, 3: 1}[mix]
     _buf(dst, torch.uint8, "dst", min_bytes=need)
-    _on_device(src=src, dst=dst)
-    st = lib().mxfp4_stream_mix(src.data_ptr(), dst.data_ptr(), wide, int(policy), mix, _stream(stream))
+    dev = _on_device(src=src, dst=dst)
+    st = lib().mxfp4_stream_mix(src.data_ptr(), dst.data_ptr(), wide, int(policy), mix, _stream(stream, dev))
     _check("mxfp4_stream_mix", st)
     return dst
 
@@ -370,8 +381,8 @@ def mxfp4_tile_copy(src, dst, stream=None):
     if src.dim() != 2 or src.shape[0] % 256 != 0 or src.shape[1] % 128 != 0:
         raise ValueError("src must be [rows % 256 == 0, row_bytes % 128 == 0]")
     _buf(dst, torch.uint8, "dst", min_bytes=src.numel())
-    _on_device(src=src, dst=dst)
-    st = lib().mxfp4_tile_copy(src.data_ptr(), dst.data_ptr(), src.shape[0], src.shape[1], _stream(stream))
+    dev = _on_device(src=src, dst=dst)
+    st = lib().mxfp4_tile_copy(src.data_ptr(), dst.data_ptr(), src.shape[0], src.shape[1], _stream(stream, dev))
     _check("mxfp4_tile_copy", st)
     return dst
 
@@ -393,8 +404,8 @@ def mxfp4_record_fanout(src, dst_idx, dst, rec_bytes=None, stream=None):
     _buf(dst, torch.uint8, "dst")
     if dst.numel() % rec != 0:
         raise ValueError("dst must hold a whole number of records")
-    _on_device(src=src, dst_idx=dst_idx, dst=dst)
+    dev = _on_device(src=src, dst_idx=dst_idx, dst=dst)
     st = lib().mxfp4_record_fanout(src.data_ptr(), ld, dst_idx.data_ptr(), M_src, dst_idx.shape[1], rec,
-                                   dst.numel() // rec, dst.data_ptr(), _stream(stream))
+                                   dst.numel() // rec, dst.data_ptr(), _stream(stream, dev))
     _check("mxfp4_record_fanout", st)
     return dst
